@@ -1,0 +1,309 @@
+"""One Gear Training sparse-part step, written out plainly.  TEST INFRASTRUCTURE ONLY.
+
+What is computed, and where the paper says so:
+
+  * A page view is a user id, a URL and several image ids (Section 1, Table 1).
+  * The Dense Part's output for an image, its Dense Feature Vector (DFV), is
+    not recomputed: it is fetched by image id from a cache that is overwritten
+    from time to time (Section 1, second point; Section 3, steps 1-3).
+  * With the DFVs in hand the Fastgear Worker runs the Sparse Part forward to
+    the loss, back-propagates through the Sparse Part only, applies the Sparse
+    Part's gradients, and keeps the gradient of the loss with respect to each
+    DFV (Section 3, step 4; Eq. 1, left factor).
+  * Each (image id, dLoss/dDFV) pair is handed to the gradient store (Section 3,
+    step 5).  Every gradient of an image is stored; when M of them have
+    arrived they are averaged and that average is what the Dense Part would
+    back-propagate (Section 1, third point; Section 3, step 6).
+
+The paper's model figure is lost, so the Sparse Part used here is the one the
+workloads name: x = [user embedding | URL embedding | mean of the view's DFVs],
+an MLP with ReLU hidden layers and one logit, sigmoid cross-entropy averaged
+over the batch, plain SGD.
+
+Arithmetic is fp64.  `round_to` is applied only where a workload *stores* a
+value in a narrower type (tables, bf16 MLP operands); see `Precision`.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import philox_normal
+from .rounding import round_to
+
+STREAM_USER = 1
+STREAM_URL = 2
+STREAM_DFV = 3
+STREAM_MLP = 16      # + layer index
+
+
+@dataclass(frozen=True)
+class Precision:
+    """Storage types.  "f64" everywhere turns every rounding off (pure mathematics)."""
+    emb: str = "f32"     # user / URL embedding rows
+    dfv: str = "f32"     # cached DFVs
+    mlp: str = "f32"     # operand type of the MLP contractions; "bf16" rounds x, W, h, delta
+    master: str = "f32"  # MLP master parameters
+
+    @staticmethod
+    def exact() -> "Precision":
+        return Precision("f64", "f64", "f64", "f64")
+
+
+class RowStore:
+    """A table of rows keyed by integer id, materialised on first use.
+
+    Either backed by an explicit dense array or by `filler(ids) -> rows`
+    (the counter-based initialiser), so that a 50M-row table costs only the
+    rows a run touches.  Rows are held as fp64 copies of the stored values.
+    """
+
+    def __init__(self, n_rows: int, dim: int, dtype: str,
+                 dense: Optional[np.ndarray] = None,
+                 filler: Optional[Callable[[np.ndarray], np.ndarray]] = None):
+        self.n_rows, self.dim, self.dtype = int(n_rows), int(dim), dtype
+        self._rows: Dict[int, np.ndarray] = {}
+        self._dense = None
+        self._filler = filler
+        if dense is not None:
+            dense = np.asarray(dense, dtype=np.float64).reshape(self.n_rows, self.dim)
+            self._dense = round_to(dense, dtype).copy()
+        elif filler is None:
+            self._dense = np.zeros((self.n_rows, self.dim))
+
+    def prefetch(self, ids: Sequence[int]) -> None:
+        if self._dense is not None:
+            return
+        need = sorted({int(i) for i in ids} - self._rows.keys())
+        if need:
+            block = round_to(np.asarray(self._filler(np.asarray(need)), dtype=np.float64), self.dtype)
+            for i, r in zip(need, block):
+                self._rows[i] = r.copy()
+
+    def row(self, i: int) -> np.ndarray:
+        i = int(i)
+        if not 0 <= i < self.n_rows:
+            raise IndexError(f"row {i} outside [0, {self.n_rows})")
+        if self._dense is not None:
+            return self._dense[i]
+        if i not in self._rows:
+            self.prefetch([i])
+        return self._rows[i]
+
+    def set_row(self, i: int, value: np.ndarray) -> None:
+        v = round_to(np.asarray(value, dtype=np.float64).reshape(self.dim), self.dtype)
+        if self._dense is not None:
+            self._dense[int(i)] = v
+        else:
+            self._rows[int(i)] = v.copy()
+
+    def rows(self, ids: Sequence[int]) -> np.ndarray:
+        self.prefetch(ids)
+        return np.stack([self.row(i) for i in ids]) if len(ids) else np.zeros((0, self.dim))
+
+
+@dataclass
+class StepResult:
+    loss: float
+    ready_ids: np.ndarray          # [n_ready] int32, ascending image id, then emission order
+    ready_grads: np.ndarray        # [n_ready x D] averaged dLoss/dDFV
+    x: np.ndarray                  # [B x F] MLP input
+    logits: np.ndarray             # [B]
+    dx: np.ndarray                 # [B x F] dLoss/dx
+    grads: List[Tuple[np.ndarray, np.ndarray]]       # (dW_l, db_l)
+    occ_grads: np.ndarray          # [nnz x D] dLoss/dDFV per occurrence, flat CSR order
+    kink_margin: np.ndarray        # [B] min over hidden units of |a| / max|a| (ReLU-kink distance)
+    user_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
+    url_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
+    img_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
+    img_segoff: np.ndarray = field(default_factory=lambda: np.zeros(1, np.int32))
+    img_perm: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
+
+
+def stable_groups(keys: np.ndarray):
+    """Distinct keys ascending, segment offsets, and the stable grouping permutation.
+
+    perm lists positions so that keys[perm] is ascending and equal keys keep
+    their original order; segment s is perm[segoff[s]:segoff[s+1]].
+    """
+    keys = np.asarray(keys)
+    buckets: Dict[int, List[int]] = {}
+    for pos, k in enumerate(keys.tolist()):
+        buckets.setdefault(k, []).append(pos)
+    uniq = sorted(buckets)
+    perm: List[int] = []
+    segoff = [0]
+    for k in uniq:
+        perm.extend(buckets[k])
+        segoff.append(len(perm))
+    return (np.asarray(uniq, dtype=np.int32), np.asarray(segoff, dtype=np.int32),
+            np.asarray(perm, dtype=np.int32))
+
+
+def bce_with_logits(z: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """-[y log s(z) + (1-y) log(1-s(z))] in the overflow-free form."""
+    return np.maximum(z, 0.0) - z * y + np.log1p(np.exp(-np.abs(z)))
+
+
+def sigmoid(z: np.ndarray) -> np.ndarray:
+    e = np.exp(-np.abs(z))
+    return np.where(z >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+
+
+class GearOracle:
+    """State of one Fastgear Worker plus the Slowgear gradient store, and `step`."""
+
+    def __init__(self, user_emb: RowStore, url_emb: RowStore, dfv: RowStore,
+                 mlp: List[Tuple[np.ndarray, np.ndarray]], M: int,
+                 precision: Precision = Precision()):
+        if M < 1:
+            raise ValueError("M must be >= 1")
+        self.user_emb, self.url_emb, self.dfv = user_emb, url_emb, dfv
+        self.prec = precision
+        self.mlp = [(round_to(np.array(W, dtype=np.float64), precision.master),
+                     round_to(np.array(b, dtype=np.float64).reshape(-1), precision.master))
+                    for W, b in mlp]
+        self.M = int(M)
+        self.d = user_emb.dim
+        self.D = dfv.dim
+        self.F = 2 * self.d + self.D
+        assert url_emb.dim == self.d and self.mlp[0][0].shape[1] == self.F
+        assert self.mlp[-1][0].shape[0] == 1
+        # Section 1, third point: every gradient of an image is kept until M have arrived.
+        self.store: Dict[int, List[np.ndarray]] = {}
+        self.counts: Dict[int, int] = {}
+
+    # ---- construction from the counter-based initialiser ------------------------------------
+    @staticmethod
+    def from_seed(seed: int, n_users: int, n_urls: int, n_images: int, emb_dim: int,
+                  dfv_dim: int, layers: Sequence[int], M: int, precision: Precision,
+                  emb_std: float = 0.01, dfv_std: float = 1.0,
+                  dfv_seed: Optional[int] = None) -> "GearOracle":
+        def filler(stream, dim, std, sd=seed):
+            return lambda ids: philox_normal.normal_rows(sd, stream, ids, dim, std)
+        user = RowStore(n_users, emb_dim, precision.emb, filler=filler(STREAM_USER, emb_dim, emb_std))
+        url = RowStore(n_urls, emb_dim, precision.emb, filler=filler(STREAM_URL, emb_dim, emb_std))
+        dfv = RowStore(n_images, dfv_dim, precision.dfv,
+                       filler=filler(STREAM_DFV, dfv_dim, dfv_std, seed if dfv_seed is None else dfv_seed))
+        mlp = []
+        fan_in = 2 * emb_dim + dfv_dim
+        for l, width in enumerate(layers):
+            W = philox_normal.normal_rows(seed, STREAM_MLP + l, np.arange(width), fan_in,
+                                          float(np.sqrt(2.0 / fan_in)))
+            mlp.append((W.astype(np.float64), np.zeros(width)))
+            fan_in = width
+        return GearOracle(user, url, dfv, mlp, M, precision)
+
+    # ---- cache refresh (Section 1, second point: cached results are overwritten) -------------
+    def refresh_dfv(self, image_ids: Sequence[int], new_rows: np.ndarray) -> None:
+        """Overwrite cached DFVs.  The gradient store and the counters live in another table
+        (Section 1, third point) and are not touched."""
+        for i, r in zip(image_ids, np.asarray(new_rows, dtype=np.float64)):
+            self.dfv.set_row(int(i), r)
+
+    def residual(self, image_id: int) -> np.ndarray:
+        """Sum of the gradients currently stored for an image (what a running sum would hold)."""
+        acc = np.zeros(self.D)
+        for g in self.store.get(int(image_id), []):
+            acc = acc + g
+        return acc
+
+    def receive(self, image_id: int, g: np.ndarray) -> Optional[np.ndarray]:
+        """Slowgear bookkeeping for one arriving gradient (Section 1, third point; Section 3,
+        step 6): keep it; once M are kept return their average and start collecting afresh."""
+        kept = self.store.setdefault(image_id, [])
+        kept.append(np.array(g, dtype=np.float64))
+        self.counts[image_id] = self.counts.get(image_id, 0) + 1
+        if len(kept) < self.M:
+            return None
+        total = np.zeros_like(kept[0])
+        for gk in kept:                                              # arrival order
+            total = total + gk
+        kept.clear()
+        return total / self.M
+
+    # ---- one training step -------------------------------------------------------------------
+    def step(self, batch, lr: float) -> StepResult:
+        B, d, D, F, M = batch.B, self.d, self.D, self.F, self.M
+        user_id, url_id = batch.user_id, batch.url_id
+        off, img_id, y = batch.img_off, batch.img_id, batch.label.astype(np.float64)
+        if off[0] != 0 or off[B] != len(img_id) or np.any(np.diff(off) < 0):
+            raise ValueError("image offsets are not a CSR index")
+        self.user_emb.prefetch(user_id)
+        self.url_emb.prefetch(url_id)
+        self.dfv.prefetch(img_id)
+
+        # 1. Sparse-Part input: embeddings and the mean of the view's cached DFVs.
+        x = np.zeros((B, F))
+        for b in range(B):
+            x[b, :d] = self.user_emb.row(user_id[b])
+            x[b, d:2 * d] = self.url_emb.row(url_id[b])
+            n_b = off[b + 1] - off[b]
+            if n_b > 0:
+                pooled = np.zeros(D)
+                for j in range(off[b], off[b + 1]):
+                    pooled = pooled + self.dfv.row(img_id[j])
+                x[b, 2 * d:] = pooled / n_b
+        x = round_to(x, self.prec.mlp)
+
+        # 2. Forward through the Sparse Part to the loss (Section 3, step 4).
+        L = len(self.mlp)
+        Wc = [round_to(W, self.prec.mlp) for W, _ in self.mlp]
+        h = [x]
+        active = [None]                                              # ReLU'(a_l): 1 where a_l > 0
+        kink = np.full(B, np.inf)
+        for l in range(L - 1):
+            a = h[l] @ Wc[l].T + self.mlp[l][1]
+            scale = np.maximum(np.abs(a).max(axis=1), np.finfo(np.float64).tiny)
+            kink = np.minimum(kink, np.abs(a).min(axis=1) / scale)
+            active.append(a > 0)
+            h.append(round_to(np.where(a > 0, a, 0.0), self.prec.mlp))
+        z = (h[L - 1] @ Wc[L - 1].T + self.mlp[L - 1][1])[:, 0]
+        loss = float(np.sum(bce_with_logits(z, y)) / B) if B else 0.0
+
+        # 3. Back-propagation through the Sparse Part only, from pre-step parameters.
+        delta = ((sigmoid(z) - y) / max(B, 1)).reshape(B, 1)       # dLoss/dz, mean reduction
+        grads: List[Tuple[np.ndarray, np.ndarray]] = [None] * L     # type: ignore
+        for l in range(L - 1, -1, -1):
+            grads[l] = (delta.T @ h[l], delta.sum(axis=0))
+            back = delta @ Wc[l]
+            if l > 0:
+                # hidden deltas are MLP operands: ReLU mask, then operand rounding
+                delta = round_to(np.where(active[l], back, 0.0), self.prec.mlp)
+            else:
+                dx = back                                            # kept unrounded
+
+        # 4. Apply the Sparse Part's gradients (plain SGD on MLP and on the touched rows).
+        self.mlp = [(round_to(W - lr * dW, self.prec.master), round_to(b - lr * db, self.prec.master))
+                    for (W, b), (dW, db) in zip(self.mlp, grads)]
+        for table, ids, lo in ((self.user_emb, user_id, 0), (self.url_emb, url_id, d)):
+            row_grad: Dict[int, np.ndarray] = {}
+            for b in range(B):                                       # batch order
+                k = int(ids[b])
+                row_grad[k] = row_grad.get(k, np.zeros(d)) + dx[b, lo:lo + d]
+            for k, g in row_grad.items():
+                table.set_row(k, table.row(k) - lr * g)
+
+        # 5. Hand every (image id, dLoss/dDFV) to the gradient store, in flat CSR order.
+        occ = np.zeros((len(img_id), D))
+        emitted: List[Tuple[int, np.ndarray]] = []
+        for b in range(B):
+            n_b = off[b + 1] - off[b]
+            for j in range(off[b], off[b + 1]):
+                occ[j] = dx[b, 2 * d:] / n_b                         # backward of the mean
+                mean = self.receive(int(img_id[j]), occ[j])
+                if mean is not None:
+                    emitted.append((int(img_id[j]), mean))
+
+        # 6. Ready list: ascending image id, emissions of one image in the order they happened.
+        order = sorted(range(len(emitted)), key=lambda e: (emitted[e][0], e))
+        ready_ids = np.asarray([emitted[e][0] for e in order], dtype=np.int32)
+        ready_grads = (np.stack([emitted[e][1] for e in order]) if order else np.zeros((0, D)))
+
+        iu, isegoff, iperm = stable_groups(img_id)
+        return StepResult(loss=loss, ready_ids=ready_ids, ready_grads=ready_grads, x=x, logits=z,
+                          dx=dx, grads=grads, occ_grads=occ, kink_margin=kink,
+                          user_unique=stable_groups(user_id)[0], url_unique=stable_groups(url_id)[0],
+                          img_unique=iu, img_segoff=isegoff, img_perm=iperm)
