@@ -1,0 +1,171 @@
+/*
+ * libgear - the Gear Training sparse-part step on one MI355X (gfx950).
+ *
+ * "Gear Training: A new way to implement high-performance model-parallel
+ * training" splits a model into a Sparse Part (user id, URL, ...) trained every
+ * step by a Fastgear Worker and a Dense Part (image CNN) owned by a Slowgear
+ * Worker.  The Dense Part is neither run forward nor backward in a training
+ * step: its outputs, the Dense Feature Vectors (DFVs), are fetched from a cache
+ * by image id (Section 1, second point; Section 3, steps 1-3), and the
+ * gradients with respect to the DFVs are collected per image until M have
+ * arrived and are then averaged (Section 1, third point; Section 3, step 6).
+ *
+ * This library is that per-step work.  All pointers named "device" are device
+ * memory owned by the caller; the library allocates nothing, keeps no state
+ * between calls, enqueues its kernels on the given hipStream_t (passed as
+ * void*) and returns without synchronising.  Results are valid once the caller
+ * has synchronised that stream.
+ *
+ * Errors.  Everything the host can check (NULL pointers, dimensions, M < 1,
+ * sizes over the configured maxima, a workspace that is too small) is reported
+ * through the return value and nothing is enqueued.  What only the device can
+ * see (an id outside its table, offsets that are not a CSR index, a ready list
+ * longer than ready_cap) is written to the device word `status`, and the step
+ * then leaves every table, accumulator and counter as it was.
+ */
+#ifndef GEAR_H
+#define GEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GEAR_MAX_LAYERS 8
+
+typedef enum gear_status {
+  GEAR_OK = 0,
+  GEAR_ERR_INVALID = 1,  /* host-checked: NULL, bad dims, M < 1, lr not finite, B or nnz over max */
+  GEAR_ERR_RANGE = 2,    /* device-checked: id out of range, offsets not a CSR index            */
+  GEAR_ERR_CAPACITY = 3, /* workspace too small (host) or ready list over ready_cap (device)    */
+  GEAR_ERR_HIP = 4       /* a HIP call failed                                                    */
+} gear_status;
+
+typedef enum gear_dtype { GEAR_F32 = 0, GEAR_BF16 = 1 } gear_dtype;
+
+/* Shape of the Sparse Part and of the tables.  Plain data, read by every call.
+ * The Sparse Part is x = [user row | URL row | mean of the view's DFVs] of width
+ * F = 2*emb_dim + dfv_dim, followed by n_layers affine layers of output widths
+ * layer_out[0..n_layers-1] with ReLU between them; the last width must be 1 (the
+ * logit).  Requirements: 2 <= n_layers <= GEAR_MAX_LAYERS, emb_dim % 8 == 0,
+ * dfv_dim % 8 == 0, hidden widths % 8 == 0. */
+typedef struct gear_config {
+  int64_t n_users, n_urls, n_images;
+  int32_t emb_dim, dfv_dim;
+  int32_t n_layers;
+  int32_t layer_out[GEAR_MAX_LAYERS];
+  int32_t emb_dtype;     /* gear_dtype of user_emb / url_emb rows                              */
+  int32_t dfv_dtype;     /* gear_dtype of dfv_cache rows                                       */
+  int32_t mlp_dtype;     /* operand type of the MLP contractions; accumulation is always fp32  */
+  int32_t max_batch;     /* largest B a step may carry                                         */
+  int32_t max_nnz;       /* largest number of (view, image) occurrences a step may carry       */
+  uint64_t seed;         /* seed of gear_init_tables                                           */
+  float emb_init_std;    /* standard deviation of the initial embedding rows                   */
+} gear_config;
+
+/* Trainable state of the Sparse Part (device).  mlp_params packs, layer after layer,
+ * W_l [layer_out[l] x in_l] row-major then b_l [layer_out[l]], all fp32 (master copy). */
+typedef struct gear_tables {
+  void *user_emb;        /* [n_users x emb_dim], emb_dtype, row-major */
+  void *url_emb;         /* [n_urls  x emb_dim], emb_dtype, row-major */
+  float *mlp_params;     /* gear_mlp_param_count(cfg) floats          */
+} gear_tables;
+
+/* One batch of page views (Section 1, Table 1: user id, URL, several image ids).
+ * All arrays are device memory.  View b owns img_id[img_off[b] .. img_off[b+1]);
+ * img_off[0] = 0, img_off[B] = nnz.  A view may have no image (its pooled DFV is 0
+ * and it produces no DFV gradient).  The same image may occur several times, also
+ * inside one view; every occurrence counts. */
+typedef struct gear_batch {
+  int32_t B, nnz;
+  const int32_t *user_id; /* [B]   in [0, n_users)        */
+  const int32_t *url_id;  /* [B]   URL hash bucket in [0, n_urls) */
+  const int32_t *img_off; /* [B+1]                         */
+  const int32_t *img_id;  /* [nnz] in [0, n_images)        */
+  const float *label;     /* [B]   click label in {0, 1}   */
+} gear_batch;
+
+/* Outputs of one step (device memory, caller-owned). */
+typedef struct gear_step_out {
+  float *loss;            /* [1] mean sigmoid cross-entropy of the batch                         */
+  int32_t *n_ready;       /* [1] number of emitted averages                                      */
+  int32_t *ready_ids;     /* [ready_cap] image ids, ascending; an image that completed several
+                             groups of M in this step appears once per group, oldest first       */
+  float *ready_grads;     /* [ready_cap x dfv_dim] fp32, row r = average for ready_ids[r]        */
+  int32_t ready_cap;      /* rows available; max_nnz is always enough                            */
+  int32_t *status;        /* [1] 0, GEAR_ERR_RANGE or GEAR_ERR_CAPACITY                          */
+  /* Optional exports of the image grouping (NULL = skip).  Sizes: [max_nnz], [max_nnz+1],
+   * [max_nnz], [1].  unique = distinct image ids ascending; segment s of the stable
+   * permutation perm is perm[segoff[s] .. segoff[s+1]), flat CSR positions ascending. */
+  int32_t *dbg_img_unique, *dbg_img_segoff, *dbg_img_perm, *dbg_n_img_unique;
+} gear_step_out;
+
+/* Bytes of scratch device memory gear_step needs for this configuration (0 on a bad config). */
+size_t gear_workspace_bytes(const gear_config *cfg);
+
+/* Number of floats in gear_tables.mlp_params, and the float offset of W_l (which = 0) or
+ * b_l (which = 1) inside it; -1 on a bad argument. */
+int64_t gear_mlp_param_count(const gear_config *cfg);
+int64_t gear_mlp_param_offset(const gear_config *cfg, int32_t layer, int32_t which);
+
+/* Byte offset and size, inside the workspace, of an intermediate of the last gear_step, for
+ * inspection by tests: "x" [B x F] mlp_dtype, "logits" [B] f32, "dx" [B x F] f32 (dLoss/dx).
+ * Returns GEAR_ERR_INVALID for an unknown name. */
+gear_status gear_workspace_region(const gear_config *cfg, const char *name, size_t *offset, size_t *bytes);
+
+/* Fill dst [n_rows x dim] (device, `dtype`) with zero-mean noise of standard deviation `std`:
+ * element (r, c) is a fixed function of (seed, stream_id, r*dim + c) - Philox4x32-10 with counter
+ * (idx_lo, idx_hi, stream_id, 0) and key (seed_lo, seed_hi); the eight 16-bit halves of its output
+ * are summed, centred, and scaled by one fp32 multiply.  (Section 4.1 fixes only a standard
+ * deviation for the initial values.) */
+gear_status gear_fill_normal(void *dst, int32_t dtype, int64_t n_rows, int32_t dim, uint64_t seed,
+                             uint32_t stream_id, float std, void *stream);
+
+/* Initial state: user_emb (stream 1) and url_emb (stream 2) ~ N(0, emb_init_std^2); W_l (stream
+ * 16+l) ~ N(0, 2/in_l), b_l = 0; grad_accum [n_images x dfv_dim] f32 and counts [n_images] i32
+ * zeroed (no gradient has arrived yet: Section 1, third point). */
+gear_status gear_init_tables(const gear_config *cfg, gear_tables *tables, float *grad_accum,
+                             int32_t *counts, void *stream);
+
+/* One Fastgear training step (Section 3, steps 4 and 5) plus the Slowgear gradient bookkeeping
+ * (Section 1, third point; Section 3, step 6; Eq. 1, left factor):
+ *   x_b   = [user_emb[user_b] | url_emb[url_b] | mean_j dfv_cache[img_j]]
+ *   loss  = mean_b BCE(sigmoid(MLP(x_b)), label_b)
+ *   MLP parameters and the touched embedding rows take one SGD step with rate lr, gradients
+ *     of a row summed over its views in batch order;
+ *   every occurrence j of image i in view b contributes g_j = dLoss/dx_b[DFV slot] / n_b;
+ *   the gradients of image i, in flat CSR order and continuing from earlier steps, are cut into
+ *     groups of M: a completed group is emitted as (i, mean of the group) and forgotten, an
+ *     unfinished one stays summed in grad_accum[i];  counts[i] += occurrences of i.
+ * dfv_cache [n_images x dfv_dim] (dfv_dtype) is read only.  grad_accum [n_images x dfv_dim] f32 and
+ * counts [n_images] i32 must be the arrays given to gear_init_tables and M must not change over
+ * their life.  workspace: gear_workspace_bytes(cfg) bytes, 256-byte aligned.  Results do not
+ * depend on the order in which the device schedules its work. */
+gear_status gear_step(const gear_config *cfg, const gear_batch *batch, gear_tables *tables,
+                      const void *dfv_cache, float *grad_accum, int32_t *counts, int32_t M, float lr,
+                      void *workspace, size_t workspace_bytes, gear_step_out *out, void *stream);
+
+/* Overwrite cached DFVs (Section 1, second point: cached inference results are replaced after the
+ * inference expired time).  Row image_ids[r] of dfv_cache becomes new_dfv[r] (device, dfv_dtype,
+ * [n x dfv_dim]); image_ids = NULL means rows 0..n-1.  Ids must be distinct.  Gradient accumulators
+ * and counters are a different table and are not touched.  status (device word, may be NULL) is
+ * set to GEAR_ERR_RANGE if an id is outside [0, n_images); such rows are skipped. */
+gear_status gear_refresh_dfv(const gear_config *cfg, void *dfv_cache, const int32_t *image_ids,
+                             const void *new_dfv, int64_t n, int32_t *status, void *stream);
+
+/* Sort-by-key grouping used for the embedding updates and the per-image accumulation, exposed
+ * for tests: keys [n] in [0, key_range) -> distinct keys ascending (unique [n]), segment offsets
+ * (segoff [n+1]), stable permutation (perm [n]) and the number of distinct keys (n_unique [1]).
+ * All device memory; workspace as for gear_step with max_batch, max_nnz >= n. */
+gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t n, int64_t key_range,
+                           void *workspace, size_t workspace_bytes, int32_t *unique, int32_t *segoff,
+                           int32_t *perm, int32_t *n_unique, void *stream);
+
+const char *gear_status_string(gear_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEAR_H */

@@ -114,7 +114,7 @@ class StepResult:
     dx: np.ndarray                 # [B x F] dLoss/dx
     grads: List[Tuple[np.ndarray, np.ndarray]]       # (dW_l, db_l)
     occ_grads: np.ndarray          # [nnz x D] dLoss/dDFV per occurrence, flat CSR order
-    kink_margin: np.ndarray        # [B] min over hidden units of |a| / max|a| (ReLU-kink distance)
+    kink_margin: np.ndarray        # [B x hidden layers] min over the layer's units of |a| / max|a|
     user_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
     url_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
     img_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
@@ -253,11 +253,11 @@ class GearOracle:
         Wc = [round_to(W, self.prec.mlp) for W, _ in self.mlp]
         h = [x]
         active = [None]                                              # ReLU'(a_l): 1 where a_l > 0
-        kink = np.full(B, np.inf)
+        kink = np.full((B, max(L - 1, 1)), np.inf)
         for l in range(L - 1):
             a = h[l] @ Wc[l].T + self.mlp[l][1]
             scale = np.maximum(np.abs(a).max(axis=1), np.finfo(np.float64).tiny)
-            kink = np.minimum(kink, np.abs(a).min(axis=1) / scale)
+            kink[:, l] = np.abs(a).min(axis=1) / scale
             active.append(a > 0)
             h.append(round_to(np.where(a > 0, a, 0.0), self.prec.mlp))
         z = (h[L - 1] @ Wc[L - 1].T + self.mlp[L - 1][1])[:, 0]

@@ -1,0 +1,375 @@
+// C ABI of libgear: argument checks, workspace layout and the launch sequence of one step.
+#include "gear_internal.hpp"
+
+#include <math.h>
+#include <string.h>
+
+namespace gear {
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t take(size_t *cursor, size_t bytes) {
+  const size_t at = *cursor;
+  *cursor = (at + bytes + kAlign - 1) / kAlign * kAlign;
+  return at;
+}
+
+int splitk_for(int M, int N, int K) {
+  const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+  int s = (768 + tiles - 1) / tiles;
+  int cap = K / 512;
+  if (cap < 1) cap = 1;
+  if (s > cap) s = cap;
+  if (s > 64) s = 64;
+  return s < 1 ? 1 : s;
+}
+
+int bits_for(int64_t range) {
+  int b = 1;
+  while (b < 31 && ((int64_t)1 << b) < range) ++b;
+  return b;
+}
+
+GroupProblem make_problem(const Layout &lay, char *ws, int slot, const int32_t *keys, int n, int64_t range) {
+  GroupProblem p;
+  memset(&p, 0, sizeof(p));
+  p.keys_in = keys;
+  p.n = n;
+  p.key_bits = bits_for(range);
+  p.passes = (p.key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
+  p.digit_bits = (p.key_bits + p.passes - 1) / p.passes;
+  const Layout::G &g = lay.g[slot];
+  for (int i = 0; i < 2; ++i) {
+    p.keys[i] = (int32_t *)(ws + g.keys[i]);
+    p.vals[i] = (int32_t *)(ws + g.vals[i]);
+  }
+  p.block_hist = (int32_t *)(ws + g.block_hist);
+  p.sorted_keys = p.keys[p.passes & 1];
+  p.perm = p.vals[p.passes & 1];
+  p.tile_heads = (int32_t *)(ws + g.tile_heads);
+  p.unique = (int32_t *)(ws + g.unique);
+  p.segoff = (int32_t *)(ws + g.segoff);
+  p.pos_seg = (int32_t *)(ws + g.pos_seg);
+  p.n_unique = (int32_t *)(ws + g.n_unique);
+  return p;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+bool config_ok(const gear_config &c) {
+  if (c.n_users < 1 || c.n_urls < 1 || c.n_images < 1) return false;
+  if (c.n_users > INT32_MAX || c.n_urls > INT32_MAX || c.n_images > INT32_MAX) return false;
+  if (c.emb_dim < 8 || c.emb_dim % 8 || c.dfv_dim < 8 || c.dfv_dim % 8) return false;
+  if (c.n_layers < 2 || c.n_layers > GEAR_MAX_LAYERS) return false;
+  for (int l = 0; l < c.n_layers - 1; ++l)
+    if (c.layer_out[l] < 8 || c.layer_out[l] % 8) return false;
+  if (c.layer_out[c.n_layers - 1] != 1) return false;
+  for (int dt : {c.emb_dtype, c.dfv_dtype, c.mlp_dtype})
+    if (dt != GEAR_F32 && dt != GEAR_BF16) return false;
+  if (c.max_batch < 1 || c.max_nnz < 1) return false;
+  if (!(c.emb_init_std >= 0.0f) || !isfinite(c.emb_init_std)) return false;
+  return true;
+}
+
+bool make_layout(const gear_config &c, Layout *lay) {
+  if (!config_ok(c)) return false;
+  memset(lay, 0, sizeof(*lay));
+  const int L = c.n_layers, F = 2 * c.emb_dim + c.dfv_dim;
+  const size_t B = (size_t)c.max_batch, NNZ = (size_t)c.max_nnz;
+  lay->F = F;
+  lay->L = L;
+  lay->act_bytes = dtype_bytes(c.mlp_dtype);
+  int64_t off = 0;
+  for (int l = 0; l < L; ++l) {
+    lay->in_dim[l] = l == 0 ? F : c.layer_out[l - 1];
+    lay->out_dim[l] = c.layer_out[l];
+    lay->w_off[l] = off;
+    off += (int64_t)lay->in_dim[l] * lay->out_dim[l];
+    lay->b_off[l] = off;
+    off += lay->out_dim[l];
+  }
+  lay->n_params = off;
+  lay->colsum_chunks = (c.max_batch + kColsumRows - 1) / kColsumRows;
+
+  size_t cur = 0;
+  const size_t ab = lay->act_bytes;
+  lay->x = take(&cur, B * F * ab);
+  size_t max_partial = 0, max_h = 1;
+  for (int l = 0; l < L; ++l) {
+    const size_t wn = (size_t)lay->in_dim[l] * lay->out_dim[l];
+    lay->wc[l] = take(&cur, wn * ab);
+    lay->wct[l] = take(&cur, wn * ab);
+    if (l < L - 1) {
+      lay->h[l] = take(&cur, B * lay->out_dim[l] * ab);
+      lay->delta[l] = take(&cur, B * lay->out_dim[l] * ab);
+      lay->splitk[l] = splitk_for(lay->out_dim[l], lay->in_dim[l], c.max_batch);
+      const size_t pb = (size_t)lay->splitk[l] * wn * sizeof(float);
+      if (pb > max_partial) max_partial = pb;
+    }
+    if ((size_t)lay->out_dim[l] > max_h) max_h = lay->out_dim[l];
+    if ((size_t)lay->in_dim[l] > max_h) max_h = lay->in_dim[l];
+  }
+  lay->logits = take(&cur, B * sizeof(float));
+  lay->dz = take(&cur, B * sizeof(float));
+  lay->loss_partial = take(&cur, kLossBlocks * sizeof(float));
+  lay->dx = take(&cur, B * F * sizeof(float));
+  lay->wgrad_partial = take(&cur, max_partial);
+  lay->colsum_partial = take(&cur, (size_t)lay->colsum_chunks * max_h * sizeof(float));
+  lay->occ_view = take(&cur, NNZ * sizeof(int32_t));
+  for (int s = 0; s < kMaxProblems; ++s) {
+    const size_t n = s == 2 ? NNZ : B;
+    const size_t tiles = (n + kSortTile - 1) / kSortTile;
+    Layout::G &g = lay->g[s];
+    for (int i = 0; i < 2; ++i) {
+      g.keys[i] = take(&cur, n * sizeof(int32_t));
+      g.vals[i] = take(&cur, n * sizeof(int32_t));
+    }
+    g.block_hist = take(&cur, (tiles + 1) * kMaxRadix * sizeof(int32_t));
+    g.tile_heads = take(&cur, tiles * sizeof(int32_t));
+    g.unique = take(&cur, n * sizeof(int32_t));
+    g.segoff = take(&cur, (n + 1) * sizeof(int32_t));
+    g.pos_seg = take(&cur, n * sizeof(int32_t));
+    g.n_unique = take(&cur, sizeof(int32_t));
+  }
+  const size_t tiles = (NNZ + kSortTile - 1) / kSortTile;
+  lay->tile_units = take(&cur, tiles * sizeof(int32_t));
+  lay->tile_emits = take(&cur, tiles * sizeof(int32_t));
+  lay->unit_q0 = take(&cur, NNZ * sizeof(int32_t));
+  lay->unit_slot = take(&cur, NNZ * sizeof(int32_t));
+  lay->unit_seg = take(&cur, NNZ * sizeof(int32_t));
+  lay->n_units = take(&cur, sizeof(int32_t));
+  lay->total = cur;
+  return true;
+}
+
+}  // namespace gear
+
+using namespace gear;
+
+#define GEAR_HIP(expr)                         \
+  do {                                         \
+    if ((expr) != hipSuccess) return GEAR_ERR_HIP; \
+  } while (0)
+
+extern "C" {
+
+size_t gear_workspace_bytes(const gear_config *cfg) {
+  Layout lay;
+  if (!cfg || !make_layout(*cfg, &lay)) return 0;
+  return lay.total;
+}
+
+int64_t gear_mlp_param_count(const gear_config *cfg) {
+  Layout lay;
+  if (!cfg || !make_layout(*cfg, &lay)) return -1;
+  return lay.n_params;
+}
+
+int64_t gear_mlp_param_offset(const gear_config *cfg, int32_t layer, int32_t which) {
+  Layout lay;
+  if (!cfg || !make_layout(*cfg, &lay) || layer < 0 || layer >= lay.L || which < 0 || which > 1) return -1;
+  return which == 0 ? lay.w_off[layer] : lay.b_off[layer];
+}
+
+gear_status gear_workspace_region(const gear_config *cfg, const char *name, size_t *offset, size_t *bytes) {
+  Layout lay;
+  if (!cfg || !name || !offset || !bytes || !make_layout(*cfg, &lay)) return GEAR_ERR_INVALID;
+  const size_t B = (size_t)cfg->max_batch;
+  if (!strcmp(name, "x")) {
+    *offset = lay.x;
+    *bytes = B * lay.F * lay.act_bytes;
+  } else if (!strcmp(name, "logits")) {
+    *offset = lay.logits;
+    *bytes = B * sizeof(float);
+  } else if (!strcmp(name, "dx")) {
+    *offset = lay.dx;
+    *bytes = B * lay.F * sizeof(float);
+  } else {
+    return GEAR_ERR_INVALID;
+  }
+  return GEAR_OK;
+}
+
+gear_status gear_fill_normal(void *dst, int32_t dtype, int64_t n_rows, int32_t dim, uint64_t seed,
+                             uint32_t stream_id, float std, void *stream) {
+  if (!dst || n_rows < 0 || dim < 1 || (dtype != GEAR_F32 && dtype != GEAR_BF16) || !(std >= 0.0f) || !isfinite(std))
+    return GEAR_ERR_INVALID;
+  GEAR_HIP(launch_fill_normal(dst, dtype, n_rows * dim, seed, stream_id, std, (hipStream_t)stream));
+  return GEAR_OK;
+}
+
+gear_status gear_init_tables(const gear_config *cfg, gear_tables *t, float *grad_accum, int32_t *counts,
+                             void *stream) {
+  Layout lay;
+  if (!cfg || !t || !t->user_emb || !t->url_emb || !t->mlp_params || !grad_accum || !counts) return GEAR_ERR_INVALID;
+  if (!make_layout(*cfg, &lay) || !aligned16(grad_accum) || !aligned16(counts) || !aligned16(t->mlp_params))
+    return GEAR_ERR_INVALID;
+  hipStream_t s = (hipStream_t)stream;
+  GEAR_HIP(launch_fill_normal(t->user_emb, cfg->emb_dtype, cfg->n_users * cfg->emb_dim, cfg->seed, 1u,
+                              cfg->emb_init_std, s));
+  GEAR_HIP(launch_fill_normal(t->url_emb, cfg->emb_dtype, cfg->n_urls * cfg->emb_dim, cfg->seed, 2u,
+                              cfg->emb_init_std, s));
+  GEAR_HIP(launch_fill_zero(t->mlp_params, (size_t)lay.n_params * sizeof(float), s));
+  for (int l = 0; l < lay.L; ++l)
+    GEAR_HIP(launch_fill_normal(t->mlp_params + lay.w_off[l], GEAR_F32, (int64_t)lay.in_dim[l] * lay.out_dim[l],
+                                cfg->seed, 16u + (uint32_t)l, sqrtf(2.0f / (float)lay.in_dim[l]), s));
+  GEAR_HIP(launch_fill_zero(grad_accum, (size_t)cfg->n_images * cfg->dfv_dim * sizeof(float), s));
+  GEAR_HIP(launch_fill_zero(counts, (size_t)cfg->n_images * sizeof(int32_t), s));
+  return GEAR_OK;
+}
+
+gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *t, const void *dfv_cache,
+                      float *grad_accum, int32_t *counts, int32_t M, float lr, void *workspace,
+                      size_t workspace_bytes, gear_step_out *out, void *stream) {
+  Layout lay;
+  if (!cfg || !b || !t || !dfv_cache || !grad_accum || !counts || !workspace || !out) return GEAR_ERR_INVALID;
+  if (!make_layout(*cfg, &lay)) return GEAR_ERR_INVALID;
+  if (!t->user_emb || !t->url_emb || !t->mlp_params) return GEAR_ERR_INVALID;
+  if (!out->loss || !out->n_ready || !out->ready_ids || !out->ready_grads || !out->status || out->ready_cap < 0)
+    return GEAR_ERR_INVALID;
+  if (M < 1 || !isfinite(lr)) return GEAR_ERR_INVALID;
+  if (b->B < 0 || b->nnz < 0 || b->B > cfg->max_batch || b->nnz > cfg->max_nnz) return GEAR_ERR_INVALID;
+  if (b->B > 0 && (!b->user_id || !b->url_id || !b->img_off || !b->label)) return GEAR_ERR_INVALID;
+  if (b->nnz > 0 && (!b->img_id || b->B == 0)) return GEAR_ERR_INVALID;
+  if (((uintptr_t)workspace & (kAlign - 1)) || !aligned16(grad_accum) || !aligned16(out->ready_grads) ||
+      !aligned16(dfv_cache) || !aligned16(t->user_emb) || !aligned16(t->url_emb))
+    return GEAR_ERR_INVALID;
+  if (workspace_bytes < lay.total) return GEAR_ERR_CAPACITY;
+
+  hipStream_t s = (hipStream_t)stream;
+  char *ws = (char *)workspace;
+  const int B = b->B, L = lay.L, F = lay.F, dt = cfg->mlp_dtype;
+  int32_t *status = out->status;
+
+  GEAR_HIP(launch_begin(status, out->n_ready, out->loss, s));
+  if (B == 0) return GEAR_OK;
+  int32_t *occ_view = (int32_t *)(ws + lay.occ_view);
+  GEAR_HIP(launch_validate(*cfg, *b, occ_view, status, s));
+
+  // grouping of the three id lists and the plan of the per-image accumulation
+  GroupBatch gb;
+  gb.count = 3;
+  gb.p[0] = make_problem(lay, ws, 0, b->user_id, B, cfg->n_users);
+  gb.p[1] = make_problem(lay, ws, 1, b->url_id, B, cfg->n_urls);
+  gb.p[2] = make_problem(lay, ws, 2, b->img_id, b->nnz, cfg->n_images);
+  GEAR_HIP(launch_group(gb, status, s));
+  AccumPlan plan;
+  plan.tile_units = (int32_t *)(ws + lay.tile_units);
+  plan.tile_emits = (int32_t *)(ws + lay.tile_emits);
+  plan.unit_q0 = (int32_t *)(ws + lay.unit_q0);
+  plan.unit_slot = (int32_t *)(ws + lay.unit_slot);
+  plan.unit_seg = (int32_t *)(ws + lay.unit_seg);
+  plan.n_units = (int32_t *)(ws + lay.n_units);
+  GEAR_HIP(launch_accum_plan(gb.p[2], plan, counts, M, out->ready_cap, out->n_ready, status, s));
+
+  // forward
+  void *x = ws + lay.x;
+  GEAR_HIP(launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
+  for (int l = 0; l < L; ++l)
+    GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt, ws + lay.wc[l],
+                                 ws + lay.wct[l], status, s));
+  for (int l = 0; l < L - 1; ++l)
+    GEAR_HIP(launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l], lay.in_dim[l],
+                            EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr, ws + lay.h[l], status, s));
+  float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
+  GEAR_HIP(launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1], b->label, B,
+                             lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial),
+                             out->loss, status, s));
+
+  // backward through the hidden layers down to dLoss/dx (all from the pre-step operand copies)
+  float *dx = (float *)(ws + lay.dx);
+  for (int l = L - 2; l >= 0; --l) {
+    if (l > 0)
+      GEAR_HIP(launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l], EPI_MASK,
+                              nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1], status, s));
+    else
+      GEAR_HIP(launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_F32, nullptr, nullptr,
+                              dx, status, s));
+  }
+
+  // SGD on the MLP: logit layer by weighted column sums, hidden layers by split-K wgrad
+  float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
+  GEAR_HIP(launch_colsum_sgd(dt, ws + lay.h[L - 2], dz, B, lay.in_dim[L - 1], cpart, t->mlp_params + lay.w_off[L - 1],
+                             lr, status, s));
+  GEAR_HIP(launch_colsum_sgd(GEAR_F32, dz, nullptr, B, 1, cpart, t->mlp_params + lay.b_off[L - 1], lr, status, s));
+  for (int l = L - 2; l >= 0; --l) {
+    const int splits = splitk_for(lay.out_dim[l], lay.in_dim[l], B);
+    GEAR_HIP(launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
+                                   lay.in_dim[l], B, splits, wpart, status, s));
+    GEAR_HIP(launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l], t->mlp_params + lay.w_off[l],
+                               lr, status, s));
+    GEAR_HIP(launch_colsum_sgd(dt, ws + lay.delta[l], nullptr, B, lay.out_dim[l], cpart, t->mlp_params + lay.b_off[l],
+                               lr, status, s));
+  }
+
+  // SGD on the touched embedding rows, then the per-image gradient bookkeeping
+  GEAR_HIP(launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb, lr, status, s));
+  GEAR_HIP(launch_accumulate(*cfg, gb.p[2], plan, occ_view, b->img_off, dx, F, grad_accum, counts, M, out->ready_ids,
+                             out->ready_grads, status, s));
+  GEAR_HIP(launch_count_update(gb.p[2], counts, status, s));
+
+  if (out->dbg_img_unique)
+    GEAR_HIP(hipMemcpyAsync(out->dbg_img_unique, gb.p[2].unique, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
+  if (out->dbg_img_segoff)
+    GEAR_HIP(hipMemcpyAsync(out->dbg_img_segoff, gb.p[2].segoff, ((size_t)b->nnz + 1) * 4, hipMemcpyDeviceToDevice, s));
+  if (out->dbg_img_perm)
+    GEAR_HIP(hipMemcpyAsync(out->dbg_img_perm, gb.p[2].perm, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
+  if (out->dbg_n_img_unique)
+    GEAR_HIP(hipMemcpyAsync(out->dbg_n_img_unique, gb.p[2].n_unique, 4, hipMemcpyDeviceToDevice, s));
+  return GEAR_OK;
+}
+
+gear_status gear_refresh_dfv(const gear_config *cfg, void *dfv_cache, const int32_t *image_ids, const void *new_dfv,
+                             int64_t n, int32_t *status, void *stream) {
+  if (!cfg || !config_ok(*cfg) || !dfv_cache || n < 0 || (n > 0 && !new_dfv)) return GEAR_ERR_INVALID;
+  if (!aligned16(dfv_cache) || !aligned16(new_dfv)) return GEAR_ERR_INVALID;
+  if (!image_ids && n > cfg->n_images) return GEAR_ERR_INVALID;
+  GEAR_HIP(launch_refresh(cfg->dfv_dtype, dfv_cache, cfg->n_images, cfg->dfv_dim, image_ids, new_dfv, n, status,
+                          (hipStream_t)stream));
+  return GEAR_OK;
+}
+
+gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t n, int64_t key_range, void *workspace,
+                           size_t workspace_bytes, int32_t *unique, int32_t *segoff, int32_t *perm, int32_t *n_unique,
+                           void *stream) {
+  Layout lay;
+  if (!cfg || !make_layout(*cfg, &lay) || !workspace || !unique || !segoff || !perm || !n_unique)
+    return GEAR_ERR_INVALID;
+  if (n < 0 || n > cfg->max_nnz || (n > 0 && !keys) || key_range < 1 || key_range > ((int64_t)1 << 31))
+    return GEAR_ERR_INVALID;
+  if ((uintptr_t)workspace & (kAlign - 1)) return GEAR_ERR_INVALID;
+  if (workspace_bytes < lay.total) return GEAR_ERR_CAPACITY;
+  hipStream_t s = (hipStream_t)stream;
+  char *ws = (char *)workspace;
+  int32_t *status = (int32_t *)(ws + lay.n_units);  // a spare word, cleared below: nothing can fail here
+  GEAR_HIP(launch_fill_zero(status, sizeof(int32_t), s));
+  GroupBatch gb;
+  gb.count = 1;
+  gb.p[0] = make_problem(lay, ws, 2, keys, n, key_range);
+  gb.p[0].pos_seg = nullptr;
+  GEAR_HIP(launch_group(gb, status, s));
+  if (n > 0) {
+    GEAR_HIP(hipMemcpyAsync(unique, gb.p[0].unique, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
+    GEAR_HIP(hipMemcpyAsync(perm, gb.p[0].perm, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
+  }
+  GEAR_HIP(hipMemcpyAsync(segoff, gb.p[0].segoff, ((size_t)n + 1) * 4, hipMemcpyDeviceToDevice, s));
+  GEAR_HIP(hipMemcpyAsync(n_unique, gb.p[0].n_unique, 4, hipMemcpyDeviceToDevice, s));
+  return GEAR_OK;
+}
+
+const char *gear_status_string(gear_status st) {
+  switch (st) {
+    case GEAR_OK: return "ok";
+    case GEAR_ERR_INVALID: return "invalid argument";
+    case GEAR_ERR_RANGE: return "id out of range or offsets not a CSR index";
+    case GEAR_ERR_CAPACITY: return "workspace or ready list too small";
+    case GEAR_ERR_HIP: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Sparse-Part input: x_b = [user_emb[user_b] | url_emb[url_b] | mean of the view's cached DFVs].
+//
+// The Dense Part is not evaluated during a step; its outputs are fetched from the cache by image
+// id (Section 1, second point; Section 3, steps 1-3).  How the DFVs of a view's several images
+// (Section 1: "multiple Image ID for one page view") meet the sparse features is in the paper's
+// lost model figure; the workloads fix it as a mean over the view's images.
+//
+// One wavefront per page view.  A lane owns 16-byte pieces of the row, so a DFV row is read with
+// fully coalesced 1 KB wave loads, several images in flight; the sum runs in fp32 in CSR order.
+#include "gear_internal.hpp"
+
+namespace gear {
+namespace {
+
+template <typename ET, typename DT, typename XT>
+__global__ void __launch_bounds__(256)
+k_gather_pool(int B, int d, int D, const int32_t *__restrict__ user_id, const int32_t *__restrict__ url_id,
+              const int32_t *__restrict__ img_off, const int32_t *__restrict__ img_id, const ET *__restrict__ user_emb,
+              const ET *__restrict__ url_emb, const DT *__restrict__ dfv, XT *__restrict__ x,
+              const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int view = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave));
+  if (view >= B) return;
+  const int F = 2 * d + D;
+  XT *xrow = x + (size_t)view * F;
+
+  // embeddings: 16-byte pieces of the two rows
+  {
+    constexpr int EN = Vec16<ET>::N;
+    const int pieces = d / EN;  // per table
+    for (int p = lane; p < 2 * pieces; p += kWave) {
+      const bool second = p >= pieces;
+      const int col = (second ? p - pieces : p) * EN;
+      const int64_t id = second ? url_id[view] : user_id[view];
+      const ET *src = (second ? url_emb : user_emb) + id * d + col;
+      Vec16<ET> v;
+      v.v = *reinterpret_cast<const decltype(v.v) *>(src);
+      XT *dst = xrow + (second ? d : 0) + col;
+#pragma unroll
+      for (int e = 0; e < EN; ++e) dst[e] = from_f32<XT>(v.get(e));
+    }
+  }
+
+  // mean of the view's DFV rows
+  constexpr int DN = Vec16<DT>::N;
+  const int lo = img_off[view], hi = img_off[view + 1];
+  const float inv = hi > lo ? 1.0f / (float)(hi - lo) : 0.0f;
+  for (int col = lane * DN; col < D; col += kWave * DN) {
+    float acc[DN];
+#pragma unroll
+    for (int e = 0; e < DN; ++e) acc[e] = 0.0f;
+    int j = lo;
+    for (; j + 4 <= hi; j += 4) {  // four rows in flight
+      Vec16<DT> v0, v1, v2, v3;
+      const int64_t i0 = img_id[j], i1 = img_id[j + 1], i2 = img_id[j + 2], i3 = img_id[j + 3];
+      v0.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i0 * D + col);
+      v1.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i1 * D + col);
+      v2.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i2 * D + col);
+      v3.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i3 * D + col);
+#pragma unroll
+      for (int e = 0; e < DN; ++e) acc[e] = (((acc[e] + v0.get(e)) + v1.get(e)) + v2.get(e)) + v3.get(e);
+    }
+    for (; j < hi; ++j) {
+      Vec16<DT> v0;
+      const int64_t i0 = img_id[j];
+      v0.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i0 * D + col);
+#pragma unroll
+      for (int e = 0; e < DN; ++e) acc[e] += v0.get(e);
+    }
+    XT *dst = xrow + 2 * d + col;
+#pragma unroll
+    for (int e = 0; e < DN; ++e) dst[e] = from_f32<XT>(acc[e] * inv);
+  }
+}
+
+template <typename ET, typename DT, typename XT>
+hipError_t run(const gear_config &cfg, const gear_batch &b, const gear_tables &t, const void *dfv, void *x,
+               const int32_t *status, hipStream_t s) {
+  const int waves = 4;
+  hipLaunchKernelGGL((k_gather_pool<ET, DT, XT>), dim3((b.B + waves - 1) / waves), dim3(waves * kWave), 0, s, b.B,
+                     cfg.emb_dim, cfg.dfv_dim, b.user_id, b.url_id, b.img_off, b.img_id, (const ET *)t.user_emb,
+                     (const ET *)t.url_emb, (const DT *)dfv, (XT *)x, status);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gather_pool(const gear_config &cfg, const gear_batch &b, const gear_tables &t, const void *dfv,
+                              void *x, const int32_t *status, hipStream_t s) {
+  if (b.B <= 0) return hipSuccess;
+  const int key = (cfg.emb_dtype << 2) | (cfg.dfv_dtype << 1) | cfg.mlp_dtype;
+  switch (key) {
+    case 0: return run<float, float, float>(cfg, b, t, dfv, x, status, s);
+    case 1: return run<float, float, bf16_t>(cfg, b, t, dfv, x, status, s);
+    case 2: return run<float, bf16_t, float>(cfg, b, t, dfv, x, status, s);
+    case 3: return run<float, bf16_t, bf16_t>(cfg, b, t, dfv, x, status, s);
+    case 4: return run<bf16_t, float, float>(cfg, b, t, dfv, x, status, s);
+    case 5: return run<bf16_t, float, bf16_t>(cfg, b, t, dfv, x, status, s);
+    case 6: return run<bf16_t, bf16_t, float>(cfg, b, t, dfv, x, status, s);
+    default: return run<bf16_t, bf16_t, bf16_t>(cfg, b, t, dfv, x, status, s);
+  }
+}
+
+}  // namespace gear

@@ -1,0 +1,190 @@
+// Internal declarations shared by the libgear translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gear.h"
+
+namespace gear {
+
+// ------------------------------------------------------------------------------------------------
+// storage types
+// ------------------------------------------------------------------------------------------------
+using bf16_t = uint16_t;  // raw bfloat16 bits: sign, 8 exponent bits, 7 fraction bits
+
+__host__ __device__ inline size_t dtype_bytes(int dt) { return dt == GEAR_BF16 ? 2 : 4; }
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round to nearest, ties to even
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// 16-byte vector of T
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  float4 v;
+  __device__ __forceinline__ float get(int i) const { return (&v.x)[i]; }
+  __device__ __forceinline__ void set(int i, float f) { (&v.x)[i] = f; }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  uint4 v;
+  __device__ __forceinline__ float get(int i) const {
+    uint32_t w = (&v.x)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+  __device__ __forceinline__ void set(int i, float f) {
+    uint32_t b = f32_to_bf16(f);
+    uint32_t &w = (&v.x)[i >> 1];
+    w = (i & 1) ? ((w & 0x0000ffffu) | (b << 16)) : ((w & 0xffff0000u) | b);
+  }
+};
+
+constexpr int kWave = 64;
+
+// ------------------------------------------------------------------------------------------------
+// grouping (sort by key + segments) problem descriptors
+// ------------------------------------------------------------------------------------------------
+constexpr int kSortBlock = 256;                       // threads
+constexpr int kSortItems = 8;                         // keys per thread
+constexpr int kSortTile = kSortBlock * kSortItems;    // keys per workgroup
+constexpr int kMaxRadixBits = 9;
+constexpr int kMaxRadix = 1 << kMaxRadixBits;
+constexpr int kMaxProblems = 3;
+
+struct GroupProblem {
+  const int32_t *keys_in;  // [n] original keys (read by the first pass)
+  int32_t n;
+  int32_t key_bits;        // significant bits of a key
+  int32_t passes;          // radix passes
+  int32_t digit_bits;      // bits per pass
+  int32_t *keys[2];        // ping-pong key buffers [n]
+  int32_t *vals[2];        // ping-pong position buffers [n]
+  int32_t *block_hist;     // [n_tiles x radix] digit counts per tile, then exclusive offsets
+  int32_t *sorted_keys;    // = keys[passes & 1]
+  int32_t *perm;           // = vals[passes & 1]
+  int32_t *tile_heads;     // [n_tiles] number of segment heads per tile
+  int32_t *unique;         // [n]   distinct keys ascending
+  int32_t *segoff;         // [n+1] segment offsets
+  int32_t *pos_seg;        // [n]   segment index of each sorted position (may be NULL)
+  int32_t *n_unique;       // [1]
+};
+
+struct GroupBatch {
+  GroupProblem p[kMaxProblems];
+  int32_t count;
+};
+
+// plan of the windowed accumulation over the sorted image occurrences
+struct AccumPlan {
+  int32_t *tile_units;   // [n_tiles] unit heads per tile
+  int32_t *tile_emits;   // [n_tiles] completed groups per tile
+  int32_t *unit_q0;      // [nnz] first sorted position of a unit
+  int32_t *unit_slot;    // [nnz] ready-list slot of the unit's emission
+  int32_t *unit_seg;     // [nnz] segment (distinct image) the unit belongs to
+  int32_t *n_units;      // [1]
+};
+
+// ------------------------------------------------------------------------------------------------
+// workspace layout (byte offsets from a 256-byte aligned base)
+// ------------------------------------------------------------------------------------------------
+struct Layout {
+  int32_t F;                         // MLP input width
+  int32_t L;                         // layers
+  int32_t in_dim[GEAR_MAX_LAYERS];   // input width of each layer
+  int32_t out_dim[GEAR_MAX_LAYERS];
+  int64_t w_off[GEAR_MAX_LAYERS];    // float offsets into mlp_params
+  int64_t b_off[GEAR_MAX_LAYERS];
+  int64_t n_params;
+  int32_t splitk[GEAR_MAX_LAYERS];   // wgrad split count per layer
+  int32_t colsum_chunks;             // row chunks of the column-sum kernels
+  size_t act_bytes;                  // sizeof(mlp_dtype)
+
+  size_t x, h[GEAR_MAX_LAYERS], delta[GEAR_MAX_LAYERS], logits, dz, loss_partial, dx;
+  size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial;
+  size_t occ_view;
+  struct G {
+    size_t keys[2], vals[2], block_hist, tile_heads, unique, segoff, pos_seg, n_unique;
+  } g[kMaxProblems];
+  size_t tile_units, tile_emits, unit_q0, unit_slot, unit_seg, n_units;
+  size_t total;
+};
+
+bool make_layout(const gear_config &cfg, Layout *lay);
+bool config_ok(const gear_config &cfg);
+
+constexpr int kColsumRows = 512;     // rows per partial of a column sum
+constexpr int kLossBlocks = 256;     // workgroups (and partial sums) of the loss kernel
+
+// ------------------------------------------------------------------------------------------------
+// kernel launchers (each defined next to its kernel)
+// ------------------------------------------------------------------------------------------------
+hipError_t launch_fill_normal(void *dst, int dtype, int64_t n_elems, uint64_t seed, uint32_t stream_id,
+                              float std, hipStream_t s);
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
+
+hipError_t launch_begin(int32_t *status, int32_t *n_ready, float *loss, hipStream_t s);
+hipError_t launch_validate(const gear_config &cfg, const gear_batch &b, int32_t *occ_view, int32_t *status,
+                           hipStream_t s);
+
+hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t s);
+hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *counts, int32_t M,
+                             int32_t ready_cap, int32_t *n_ready, int32_t *status, hipStream_t s);
+
+hipError_t launch_gather_pool(const gear_config &cfg, const gear_batch &b, const gear_tables &t,
+                              const void *dfv_cache, void *x, const int32_t *status, hipStream_t s);
+
+hipError_t launch_cast_weights(const float *w, int rows, int cols, int dtype, void *wc, void *wct,
+                               const int32_t *status, hipStream_t s);
+
+enum GemmEpilogue {
+  EPI_BIAS_RELU = 0,  // out(T)   = max(acc + bias[n], 0)
+  EPI_MASK = 1,       // out(T)   = aux[m,n] > 0 ? acc : 0
+  EPI_F32 = 2,        // out(f32) = acc
+};
+// C[M x N] = A[M x K] * B[N x K]^T, both operands K-contiguous, type `dtype`.
+hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue,
+                          const float *bias, const void *aux, void *out, const int32_t *status, hipStream_t s);
+// partial[z][M x N] = sum over the z-th K range of A[K x M]^T * B[K x N] (operands M-/N-contiguous).
+hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
+                                 float *partial, const int32_t *status, hipStream_t s);
+hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, float lr,
+                             const int32_t *status, hipStream_t s);
+
+hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, const float *bias_last,
+                             const float *label, int B, int H, float *logits, float *dz, void *delta,
+                             float *loss_partial, float *loss, const int32_t *status, hipStream_t s);
+
+hipError_t launch_colsum_sgd(int dtype, const void *src, const float *row_weight, int B, int H,
+                             float *partial, float *dst, float lr, const int32_t *status, hipStream_t s);
+
+hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
+                                   const float *dx, int F, void *user_emb, void *url_emb, float lr,
+                                   const int32_t *status, hipStream_t s);
+
+hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan,
+                             const int32_t *occ_view, const int32_t *img_off, const float *dx, int F,
+                             float *grad_accum, const int32_t *counts, int32_t M, int32_t *ready_ids,
+                             float *ready_grads, const int32_t *status, hipStream_t s);
+hipError_t launch_count_update(const GroupProblem &img, int32_t *counts, const int32_t *status, hipStream_t s);
+
+hipError_t launch_refresh(int dtype, void *dfv_cache, int64_t n_images, int dim, const int32_t *ids,
+                          const void *rows, int64_t n, int32_t *status, hipStream_t s);
+
+}  // namespace gear

@@ -1,0 +1,361 @@
+// Sort-by-key grouping of a step's ids, and the plan of the per-image accumulation.
+//
+// The Sparse Part's gradients are applied per embedding row (Section 3, step 4) and the DFV
+// gradients are collected per image id (Section 3, steps 5-6).  Both need "all positions that
+// carry the same id, in their original order": a stable LSD radix sort of (id, position) pairs
+// followed by a head-flag scan gives the distinct ids, the segment offsets and the stable
+// permutation.  Up to three id lists (users, URLs, images) go through the same launches.
+//
+// Everything here is integer work whose result does not depend on scheduling: digit counts are
+// integer sums, ranks come from wave ballots in lane order, scans run in a fixed shape.
+#include "gear_internal.hpp"
+
+namespace gear {
+namespace {
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int t = __shfl_up(v, off, kWave);
+    if (lane >= off) v += t;
+  }
+  return v;
+}
+
+// exclusive scan of one int per thread over a 256-thread workgroup; *total = sum of all
+__device__ __forceinline__ int block_exclusive_scan(int v, int *total, int *smem /* >= 5 ints */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int inc = wave_inclusive_scan(v, lane);
+  __syncthreads();  // smem may still be read from a previous call
+  if (lane == 63) smem[wave] = inc;
+  __syncthreads();
+  int base = 0, sum = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int t = smem[w];
+    if (w < wave) base += t;
+    sum += t;
+  }
+  *total = sum;
+  return base + inc - v;
+}
+
+// sum of tile_vals[0 .. tile) for tile <= 256 * 4, computed by the whole workgroup
+__device__ __forceinline__ int sum_before(const int32_t *tile_vals, int tile, int *smem) {
+  int v = 0;
+  for (int t = threadIdx.x; t < tile; t += blockDim.x) v += tile_vals[t];
+  int total;
+  block_exclusive_scan(v, &total, smem);
+  return total;
+}
+
+__device__ __forceinline__ const int32_t *pass_keys(const GroupProblem &p, int pass) {
+  return pass == 0 ? p.keys_in : p.keys[pass & 1];
+}
+
+// ---- radix pass: per-tile digit histogram ----------------------------------------------------------
+__global__ void __launch_bounds__(kSortBlock) k_radix_hist(GroupBatch gb, int pass, const int32_t *status) {
+  if (*status != 0) return;
+  const GroupProblem &p = gb.p[blockIdx.y];
+  if (pass >= p.passes) return;
+  const int tile0 = blockIdx.x * kSortTile;
+  if (tile0 >= p.n) return;
+  __shared__ int hist[kMaxRadix];
+  const int radix = 1 << p.digit_bits, shift = pass * p.digit_bits;
+  for (int d = threadIdx.x; d < radix; d += kSortBlock) hist[d] = 0;
+  __syncthreads();
+  const int32_t *keys = pass_keys(p, pass);
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + i * kSortBlock + threadIdx.x;
+    if (q < p.n) atomicAdd(&hist[(keys[q] >> shift) & (radix - 1)], 1);
+  }
+  __syncthreads();
+  for (int d = threadIdx.x; d < radix; d += kSortBlock) p.block_hist[(size_t)blockIdx.x * radix + d] = hist[d];
+}
+
+// ---- radix pass: exclusive offsets.  block_hist[t][d] becomes the number of keys with digit d in
+// tiles before t; row n_tiles receives the number of keys with a smaller digit. -----------------------
+__global__ void __launch_bounds__(kMaxRadix) k_radix_scan(GroupBatch gb, int pass, const int32_t *status) {
+  if (*status != 0) return;
+  const GroupProblem &p = gb.p[blockIdx.x];
+  if (pass >= p.passes || p.n <= 0) return;
+  __shared__ int totals[kMaxRadix];
+  __shared__ int wave_tot[kMaxRadix / kWave];
+  const int radix = 1 << p.digit_bits;
+  const int n_tiles = (p.n + kSortTile - 1) / kSortTile;
+  const int d = threadIdx.x;
+  int run = 0;
+  if (d < radix) {
+    for (int t = 0; t < n_tiles; ++t) {
+      int32_t *cell = p.block_hist + (size_t)t * radix + d;
+      const int c = *cell;
+      *cell = run;
+      run += c;
+    }
+  }
+  // exclusive scan of `run` over digits (blockDim = 512 = 8 waves)
+  const int lane = d & 63, wave = d >> 6;
+  const int inc = wave_inclusive_scan(d < radix ? run : 0, lane);
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+  totals[d] = base + inc - (d < radix ? run : 0);
+  __syncthreads();
+  if (d < radix) p.block_hist[(size_t)n_tiles * radix + d] = totals[d];
+}
+
+// ---- radix pass: stable scatter ---------------------------------------------------------------------
+__global__ void __launch_bounds__(kSortBlock) k_radix_scatter(GroupBatch gb, int pass, const int32_t *status) {
+  if (*status != 0) return;
+  const GroupProblem &p = gb.p[blockIdx.y];
+  if (pass >= p.passes) return;
+  const int tile0 = blockIdx.x * kSortTile;
+  if (tile0 >= p.n) return;
+  // cnt[round][wave][digit]: keys with that digit seen by that wave in that round
+  __shared__ uint16_t cnt[kSortItems * 4 * kMaxRadix];
+  __shared__ int digit_off[kMaxRadix];
+  const int radix = 1 << p.digit_bits, shift = pass * p.digit_bits;
+  const int n_tiles = (p.n + kSortTile - 1) / kSortTile;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  for (int i = threadIdx.x; i < kSortItems * 4 * radix / 2; i += kSortBlock) reinterpret_cast<uint32_t *>(cnt)[i] = 0u;
+  for (int d = threadIdx.x; d < radix; d += kSortBlock)
+    digit_off[d] = p.block_hist[(size_t)blockIdx.x * radix + d] + p.block_hist[(size_t)n_tiles * radix + d];
+  __syncthreads();
+
+  const int32_t *keys_in = pass_keys(p, pass);
+  const int32_t *vals_in = p.vals[pass & 1];
+  int32_t key[kSortItems], val[kSortItems], rank[kSortItems];
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + i * kSortBlock + threadIdx.x;
+    const bool valid = q < p.n;
+    key[i] = valid ? keys_in[q] : 0;
+    val[i] = valid ? (pass == 0 ? q : vals_in[q]) : 0;
+    const int digit = (key[i] >> shift) & (radix - 1);
+    unsigned long long peers = __ballot(valid);
+    for (int b = 0; b < p.digit_bits; ++b) {
+      const bool bit = (digit >> b) & 1;
+      const unsigned long long m = __ballot(bit);
+      peers &= bit ? m : ~m;
+    }
+    rank[i] = __popcll(peers & ((1ull << lane) - 1ull));
+    if (valid && rank[i] == 0) cnt[(i * 4 + wave) * radix + digit] = (uint16_t)__popcll(peers);
+  }
+  __syncthreads();
+  // exclusive scan over (round, wave) for every digit
+  for (int d = threadIdx.x; d < radix; d += kSortBlock) {
+    int run = 0;
+#pragma unroll
+    for (int rw = 0; rw < kSortItems * 4; ++rw) {
+      const int c = cnt[rw * radix + d];
+      cnt[rw * radix + d] = (uint16_t)run;
+      run += c;
+    }
+  }
+  __syncthreads();
+  int32_t *keys_out = p.keys[(pass + 1) & 1];
+  int32_t *vals_out = p.vals[(pass + 1) & 1];
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + i * kSortBlock + threadIdx.x;
+    if (q < p.n) {
+      const int digit = (key[i] >> shift) & (radix - 1);
+      const int pos = digit_off[digit] + cnt[(i * 4 + wave) * radix + digit] + rank[i];
+      keys_out[pos] = key[i];
+      vals_out[pos] = val[i];
+    }
+  }
+}
+
+// ---- segments: head flags over the sorted keys ------------------------------------------------------
+// Blocked arrangement: thread t owns positions tile0 + 8 t .. + 7, so a scan keeps position order.
+__global__ void __launch_bounds__(kSortBlock) k_seg_count(GroupBatch gb, const int32_t *status) {
+  if (*status != 0) return;
+  const GroupProblem &p = gb.p[blockIdx.y];
+  const int tile0 = blockIdx.x * kSortTile;
+  if (tile0 >= p.n) return;
+  __shared__ int smem[8];
+  const int32_t *sk = p.sorted_keys;
+  int heads = 0;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    if (q < p.n) heads += (q == 0 || sk[q] != sk[q - 1]) ? 1 : 0;
+  }
+  int total;
+  block_exclusive_scan(heads, &total, smem);
+  if (threadIdx.x == 0) p.tile_heads[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(kSortBlock) k_seg_scatter(GroupBatch gb, const int32_t *status) {
+  if (*status != 0) return;
+  const GroupProblem &p = gb.p[blockIdx.y];
+  const int tile0 = blockIdx.x * kSortTile;
+  if (p.n <= 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      *p.n_unique = 0;
+      p.segoff[0] = 0;
+    }
+    return;
+  }
+  if (tile0 >= p.n) return;
+  __shared__ int smem[8];
+  const int32_t *sk = p.sorted_keys;
+  const int base = sum_before(p.tile_heads, blockIdx.x, smem);
+  bool head[kSortItems];
+  int mine = 0;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    head[i] = q < p.n && (q == 0 || sk[q] != sk[q - 1]);
+    mine += head[i] ? 1 : 0;
+  }
+  int total;
+  int idx = base + block_exclusive_scan(mine, &total, smem);
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    if (q < p.n) {
+      if (head[i]) {
+        p.unique[idx] = sk[q];
+        p.segoff[idx] = q;
+        ++idx;
+      }
+      if (p.pos_seg) p.pos_seg[q] = idx - 1;
+    }
+  }
+  if (tile0 + kSortTile >= p.n && threadIdx.x == 0) {  // last tile
+    *p.n_unique = base + total;
+    p.segoff[base + total] = p.n;
+  }
+}
+
+// ---- plan of the windowed accumulation -----------------------------------------------------------------
+// Section 1, third point: the gradients of one image are collected until M have arrived, then
+// averaged.  With c gradients already collected in earlier steps, the occurrence at in-step rank r
+// has ordinal k = c + r; ordinals kM .. kM+M-1 form one group.  A "unit" is the work of one
+// workgroup: the first (possibly partial, possibly continuing) group of an image together with its
+// unfinished last group, or one complete middle group.  An "emission" is a completed group.
+struct UnitFlags {
+  bool unit, emit;
+};
+
+__device__ __forceinline__ UnitFlags unit_flags(const GroupProblem &p, const int32_t *counts, int M, int q) {
+  const int32_t *sk = p.sorted_keys;
+  const int i = sk[q];
+  const int s0 = p.segoff[p.pos_seg[q]];
+  const int k = counts[i] + (q - s0);
+  const int ph = k % M;
+  UnitFlags f;
+  f.unit = (q == s0) || (ph == 0 && M <= p.n - q && sk[q + M - 1] == i);
+  f.emit = (ph == M - 1);
+  return f;
+}
+
+__global__ void __launch_bounds__(kSortBlock) k_plan_count(GroupProblem p, AccumPlan plan, const int32_t *counts,
+                                                           int M, const int32_t *status) {
+  if (*status != 0) return;
+  const int tile0 = blockIdx.x * kSortTile;
+  if (tile0 >= p.n) return;
+  __shared__ int smem[8];
+  int units = 0, emits = 0;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    if (q < p.n) {
+      const UnitFlags f = unit_flags(p, counts, M, q);
+      units += f.unit ? 1 : 0;
+      emits += f.emit ? 1 : 0;
+    }
+  }
+  int tu, te;
+  block_exclusive_scan(units, &tu, smem);
+  block_exclusive_scan(emits, &te, smem);
+  if (threadIdx.x == 0) {
+    plan.tile_units[blockIdx.x] = tu;
+    plan.tile_emits[blockIdx.x] = te;
+  }
+}
+
+__global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, AccumPlan plan, const int32_t *counts,
+                                                             int M, int ready_cap, int32_t *n_ready, int32_t *status) {
+  if (*status != 0) return;
+  const int tile0 = blockIdx.x * kSortTile;
+  if (p.n <= 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      *plan.n_units = 0;
+      *n_ready = 0;
+    }
+    return;
+  }
+  if (tile0 >= p.n) return;
+  __shared__ int smem[8];
+  const int base_u = sum_before(plan.tile_units, blockIdx.x, smem);
+  const int base_e = sum_before(plan.tile_emits, blockIdx.x, smem);
+  UnitFlags f[kSortItems];
+  int units = 0, emits = 0;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    f[i].unit = f[i].emit = false;
+    if (q < p.n) f[i] = unit_flags(p, counts, M, q);
+    units += f[i].unit ? 1 : 0;
+    emits += f[i].emit ? 1 : 0;
+  }
+  int tu, te;
+  int u = base_u + block_exclusive_scan(units, &tu, smem);
+  int e = base_e + block_exclusive_scan(emits, &te, smem);
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    if (q < p.n) {
+      if (f[i].unit) {
+        plan.unit_q0[u] = q;
+        plan.unit_slot[u] = e;
+        plan.unit_seg[u] = p.pos_seg[q];
+        ++u;
+      }
+      if (f[i].emit) ++e;
+    }
+  }
+  if (tile0 + kSortTile >= p.n && threadIdx.x == 0) {
+    *plan.n_units = base_u + tu;
+    *n_ready = base_e + te;
+    if (base_e + te > ready_cap) atomicCAS(status, 0, GEAR_ERR_CAPACITY);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t s) {
+  int max_tiles = 1, max_passes = 0;
+  for (int i = 0; i < gb.count; ++i) {
+    const int t = (gb.p[i].n + kSortTile - 1) / kSortTile;
+    if (t > max_tiles) max_tiles = t;
+    if (gb.p[i].n > 0 && gb.p[i].passes > max_passes) max_passes = gb.p[i].passes;
+  }
+  const dim3 grid(max_tiles, gb.count);
+  for (int pass = 0; pass < max_passes; ++pass) {
+    hipLaunchKernelGGL(k_radix_hist, grid, dim3(kSortBlock), 0, s, gb, pass, status);
+    hipLaunchKernelGGL(k_radix_scan, dim3(gb.count), dim3(kMaxRadix), 0, s, gb, pass, status);
+    hipLaunchKernelGGL(k_radix_scatter, grid, dim3(kSortBlock), 0, s, gb, pass, status);
+  }
+  hipLaunchKernelGGL(k_seg_count, grid, dim3(kSortBlock), 0, s, gb, status);
+  hipLaunchKernelGGL(k_seg_scatter, grid, dim3(kSortBlock), 0, s, gb, status);
+  return hipGetLastError();
+}
+
+hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *counts, int32_t M,
+                             int32_t ready_cap, int32_t *n_ready, int32_t *status, hipStream_t s) {
+  int tiles = (img.n + kSortTile - 1) / kSortTile;
+  if (tiles < 1) tiles = 1;
+  hipLaunchKernelGGL(k_plan_count, dim3(tiles), dim3(kSortBlock), 0, s, img, plan, counts, M, status);
+  hipLaunchKernelGGL(k_plan_scatter, dim3(tiles), dim3(kSortBlock), 0, s, img, plan, counts, M, ready_cap, n_ready,
+                     status);
+  return hipGetLastError();
+}
+
+}  // namespace gear

@@ -1,0 +1,354 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, on a real MI355X.
+
+Integer results are compared bit for bit, floating point by the row rule of oracle/compare.py
+(1e-5 relative for fp32 workloads, 2e-2 for bf16).  Both sides start from their own counter-based
+initialiser and run freely; nothing the oracle consumes comes from the GPU.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gear_inputs import PageViewSource, get_workload
+from gear_inputs.pageviews import PageViewBatch, batch_from_lists
+from oracle import philox_normal
+from oracle.compare import REL, assert_rows_close, row_errors
+from oracle.from_workload import oracle_for
+from oracle.gear_oracle import stable_groups
+from oracle.rounding import round_to
+
+pytestmark = pytest.mark.gpu
+
+g = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global g
+    import paper_1806_03925_amd as mod
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    g = mod
+    yield
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def make_pair(wl, max_batch=None, ready_cap=None):
+    cfg = g.config_for(wl, max_batch=max_batch)
+    st = g.GearState(cfg, debug=True, ready_cap=ready_cap)
+    g.gear_init_tables(st)
+    g.gear_fill_normal(st.dfv_cache, wl.n_images, wl.dfv_dim, wl.seed, 3, wl.dfv_std)
+    return cfg, st, oracle_for(wl)
+
+
+def check_step(wl, st, orc, batch: PageViewBatch, lr: float, what: str):
+    """Run one step on both sides and compare every output; returns the oracle's result."""
+    rel = REL[wl.mlp_dtype]
+    dev = g.DeviceBatch.from_host(batch)
+    g.gear_step(st, dev, wl.M, lr)
+    torch.cuda.synchronize()
+    ref = orc.step(batch, float(np.float32(lr)))
+    B, d = batch.B, wl.emb_dim
+    assert int(st.status.item()) == 0, what
+
+    # grouping of the image ids
+    nu = int(st.dbg[3].item())
+    assert nu == len(ref.img_unique), what
+    assert np.array_equal(st.dbg[0][:nu].cpu().numpy(), ref.img_unique), what
+    assert np.array_equal(st.dbg[1][:nu + 1].cpu().numpy(), ref.img_segoff), what
+    assert np.array_equal(st.dbg[2][:batch.nnz].cpu().numpy(), ref.img_perm), what
+
+    # forward
+    assert_rows_close(f64(st.region("x", B)), ref.x, rel, f"{what}: x")
+    assert_rows_close(f64(st.region("logits", B)), ref.logits, rel, f"{what}: logits")
+    assert abs(float(st.loss.item()) - ref.loss) <= rel * abs(ref.loss), (what, st.loss.item(), ref.loss)
+
+    # dLoss/dx.  A view whose hidden pre-activation lies within rounding distance of the ReLU kink
+    # may take the other branch, which moves its whole row by about 1/sqrt(active units).  In fp32
+    # the two sides differ by accumulation order only (~1e-6 of the layer's scale).  With bf16
+    # operands an element of x or h can round to the neighbouring bf16 value (2^-8 relative), which
+    # shifts the next layer's pre-activations by about 2^-8 * |w| / sqrt(fan_in) ~ 1e-3 of their
+    # scale.  Rows outside that distance must pass; inside it they may flip, but only a few do.
+    tol = 1e-5 if wl.mlp_dtype == "f32" else 2e-3
+    near_kink = (ref.kink_margin < tol).any(axis=1)
+    dx = f64(st.region("dx", B))
+    assert np.isfinite(dx).all()
+    err, scale = row_errors(dx, ref.dx)
+    failed = err > rel * scale
+    assert not (failed & ~near_kink).any(), \
+        f"{what}: dx rows off away from any kink: {np.flatnonzero(failed & ~near_kink)[:5]}"
+    cap = max(2, 0.002 * B) if wl.mlp_dtype == "f32" else max(2, 0.06 * B)
+    assert failed.sum() <= cap, f"{what}: {failed.sum()} of {B} dx rows flipped at kinks"
+    assert np.median(err / scale) <= rel / 4, f"{what}: median dx row error {np.median(err / scale):.2e}"
+    flipped_views = np.flatnonzero(failed)
+    flipped_imgs = set()
+    for b in flipped_views:
+        flipped_imgs.update(batch.img_id[batch.img_off[b]:batch.img_off[b + 1]].tolist())
+
+    # ready list and averaged gradients
+    n_ready = int(st.n_ready.item())
+    assert n_ready == len(ref.ready_ids), what
+    assert np.array_equal(st.ready_ids[:n_ready].cpu().numpy(), ref.ready_ids), what
+    if n_ready:
+        ex = np.isin(ref.ready_ids, list(flipped_imgs))
+        assert_rows_close(f64(st.ready_grads[:n_ready]), ref.ready_grads, rel, f"{what}: ready_grads", exempt=ex)
+    return ref, flipped_views, flipped_imgs
+
+
+def check_state(wl, st, orc, what, flipped_users=(), flipped_urls=(), flipped_imgs=()):
+    """Compare the persistent state: counters bit-exact, accumulators and tables by rows."""
+    rel = REL[wl.mlp_dtype]
+    counts = st.counts.cpu().numpy()
+    touched = np.array(sorted(orc.counts), dtype=np.int64)
+    assert int(counts.sum()) == sum(orc.counts.values()), what
+    assert np.array_equal(counts[touched], np.array([orc.counts[i] for i in touched], dtype=np.int32)), what
+    if len(touched):
+        acc = f64(st.grad_accum[torch.from_numpy(touched).cuda()])
+        ref = np.stack([orc.residual(i) for i in touched])
+        # images whose count is a multiple of M hold exactly zero
+        full = np.array([orc.counts[i] % wl.M == 0 for i in touched])
+        assert not acc[full].any(), what
+        assert_rows_close(acc, ref, rel, f"{what}: grad_accum", exempt=np.isin(touched, list(flipped_imgs)))
+    # untouched accumulators are still zero
+    nz_rows = int((st.grad_accum != 0).any(dim=1).sum().item())
+    assert nz_rows <= len(touched), what
+    for name, table, store, flipped in (("user_emb", st.user_emb, orc.user_emb, flipped_users),
+                                        ("url_emb", st.url_emb, orc.url_emb, flipped_urls)):
+        ids = np.array(sorted(store._rows), dtype=np.int64)
+        if len(ids):
+            got = f64(table[torch.from_numpy(ids).cuda()])
+            assert_rows_close(got, np.stack([store.row(i) for i in ids]), rel, f"{what}: {name}",
+                              exempt=np.isin(ids, list(flipped)))
+    for l, (W, b) in enumerate(orc.mlp):
+        Wg, bg = st.layer_params(l)
+        assert_rows_close(f64(Wg), W, rel, f"{what}: W{l}")
+        assert_rows_close(f64(bg), b, rel, f"{what}: b{l}")
+
+
+# ------------------------------------------------------------------ initialiser
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fill_normal_matches_generator_bit_for_bit(dtype):
+    rows, dim, seed, stream, std = 3001, 72, 0x1234_5678_9ABC_DEF0, 5, 0.37
+    t = torch.empty((rows, dim), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    g.gear_fill_normal(t, rows, dim, seed, stream, std)
+    torch.cuda.synchronize()
+    ref = round_to(philox_normal.normal_rows(seed, stream, np.arange(rows), dim, std).astype(np.float64), dtype)
+    assert np.array_equal(f64(t), ref)
+
+
+def test_init_tables_matches_oracle_state():
+    wl = get_workload("tiny")
+    cfg, st, orc = make_pair(wl)
+    torch.cuda.synchronize()
+    assert np.array_equal(f64(st.user_emb), orc.user_emb.rows(np.arange(wl.n_users)))
+    assert np.array_equal(f64(st.url_emb[:100]), orc.url_emb.rows(np.arange(100)))
+    assert np.array_equal(f64(st.dfv_cache[-50:]), orc.dfv.rows(np.arange(wl.n_images - 50, wl.n_images)))
+    for l, (W, b) in enumerate(orc.mlp):
+        Wg, bg = st.layer_params(l)
+        assert np.array_equal(f64(Wg), W) and not bg.any()
+    assert not st.grad_accum.any() and not st.counts.any()
+
+
+# ------------------------------------------------------------------ grouping
+@pytest.mark.parametrize("n,key_range", [(0, 10), (1, 10), (5, 3), (2048, 50), (2049, 1 << 26), (6000, 1),
+                                         (50_000, 4_000_000), (50_000, 700), (131_072, 50_000_000)])
+def test_group_ids_matches_brute_force(n, key_range):
+    wl = get_workload("tiny").scaled(batch=max(n, 1), max_images=1)
+    cfg = g.config_for(wl)
+    st = g.GearState(cfg)
+    rng = np.random.default_rng(n + key_range)
+    keys = rng.integers(0, key_range, n).astype(np.int32)
+    if n > 100:
+        keys[rng.integers(0, n, n // 3)] = keys[0]            # one long segment
+    unique, segoff, perm, n_unique = g.gear_group_ids(st, torch.from_numpy(keys).cuda(), key_range)
+    torch.cuda.synchronize()
+    ru, rs, rp = stable_groups(keys)
+    nu = int(n_unique.item())
+    assert nu == len(ru)
+    assert np.array_equal(unique[:nu].cpu().numpy(), ru)
+    assert np.array_equal(segoff[:nu + 1].cpu().numpy(), rs)
+    assert np.array_equal(perm[:n].cpu().numpy(), rp)
+
+
+# ------------------------------------------------------------------ full steps
+def test_tiny_all_steps_free_running():
+    wl = get_workload("tiny")
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    emitted = 0
+    for step in range(wl.steps):
+        ref, fv, fi = check_step(wl, st, orc, src.batch(step), wl.lr, f"tiny step {step}")
+        assert len(fv) == 0
+        emitted += len(ref.ready_ids)
+        check_state(wl, st, orc, f"tiny after step {step}")
+    assert emitted > 0
+
+
+@pytest.mark.parametrize("name,batch,steps,lr", [
+    ("small", 1000, 3, 0.01),        # ragged batch: 1000 = 7 * 128 + 104 views
+    ("small", 4096, 2, 2.0),         # large rate so that embedding updates are far above rounding
+    ("hotkey", 2500, 3, 0.01),       # windows crossing M several times per step
+    ("bf16", 1500, 3, 0.01),
+    ("bf16", 4096, 1, 4.0),         # one step at a rate that lifts bf16 row updates above their rounding
+    ("large", 700, 2, 0.01),
+])
+def test_workload_steps_free_running(name, batch, steps, lr):
+    wl = get_workload(name)
+    if name in ("bf16", "large"):                      # keep the oracle's tables small
+        wl = wl.scaled(n_users=200_000, n_urls=1 << 18, n_images=20_000)
+    if name == "hotkey":
+        wl = wl.scaled(n_images=300)                     # many images pass M = 64 more than once per step
+    cfg, st, orc = make_pair(wl, max_batch=batch)
+    src = PageViewSource(wl)
+    fu, fl, fi = set(), set(), set()
+    for step in range(steps):
+        b = src.batch(step, batch=batch)
+        ref, fv, imgs = check_step(wl, st, orc, b, lr, f"{name} B={batch} step {step}")
+        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
+        check_state(wl, st, orc, f"{name} B={batch} after step {step}", fu, fl, fi)
+    assert sum(orc.counts.values()) > 0
+
+
+def test_same_step_twice_is_bit_identical():
+    wl = get_workload("hotkey").scaled(n_images=500)
+    outs = []
+    for _ in range(2):
+        cfg, st, _ = make_pair(wl, max_batch=3000)
+        src = PageViewSource(wl)
+        for step in range(2):
+            g.gear_step(st, g.DeviceBatch.from_host(src.batch(step, batch=3000)), wl.M, 0.5)
+        torch.cuda.synchronize()
+        n = int(st.n_ready.item())
+        outs.append([t.clone() for t in (st.loss, st.ready_ids[:n], st.ready_grads[:n], st.grad_accum, st.counts,
+                                         st.user_emb, st.url_emb, st.mlp_params)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------ edge cases
+def test_empty_views_duplicates_and_single_view():
+    wl = get_workload("tiny").scaled(M=2)
+    cfg, st, orc = make_pair(wl)
+    b = batch_from_lists([1, 1, 7, 999], [0, 4095, 5, 5], [[], [3, 3, 3], [1999], []], [1, 0, 0, 1])
+    ref, _, _ = check_step(wl, st, orc, b, 0.5, "empty views")
+    assert ref.ready_ids.tolist() == [3]
+    check_state(wl, st, orc, "empty views")
+    b1 = batch_from_lists([0], [0], [[3, 0, 3]], [0])
+    ref, _, _ = check_step(wl, st, orc, b1, 0.5, "single view")
+    assert ref.ready_ids.tolist() == [3]             # one kept gradient + two new ones: one group of M = 2
+    check_state(wl, st, orc, "single view")
+    b2 = batch_from_lists([5, 6], [1, 2], [[], []], [0, 1])     # no image at all
+    check_step(wl, st, orc, b2, 0.5, "no occurrences")
+    check_state(wl, st, orc, "no occurrences")
+
+
+def test_batch_of_zero_views_is_a_no_op():
+    wl = get_workload("tiny")
+    cfg, st, _ = make_pair(wl)
+    before = [t.clone() for t in (st.user_emb, st.mlp_params, st.grad_accum, st.counts)]
+    e = torch.zeros(0, dtype=torch.int32, device="cuda")
+    dev = g.DeviceBatch(e, e, torch.zeros(1, dtype=torch.int32, device="cuda"), e, torch.zeros(0, device="cuda"))
+    st.n_ready.fill_(7)
+    g.gear_step(st, dev, wl.M, 0.1)
+    torch.cuda.synchronize()
+    assert int(st.n_ready.item()) == 0 and float(st.loss.item()) == 0.0 and int(st.status.item()) == 0
+    for a, b in zip(before, (st.user_emb, st.mlp_params, st.grad_accum, st.counts)):
+        assert torch.equal(a, b)
+
+
+def test_maximum_batch_and_nnz():
+    wl = get_workload("tiny")
+    cfg, st, orc = make_pair(wl)
+    rng = np.random.default_rng(9)
+    views = [rng.integers(0, wl.n_images, wl.max_images).tolist() for _ in range(wl.batch)]   # nnz = max_nnz
+    b = batch_from_lists(rng.integers(0, wl.n_users, wl.batch), rng.integers(0, wl.n_urls, wl.batch), views,
+                         rng.integers(0, 2, wl.batch))
+    assert b.nnz == cfg.max_nnz
+    check_step(wl, st, orc, b, 0.1, "max sizes")
+    check_state(wl, st, orc, "max sizes")
+
+
+def test_bad_ids_are_reported_and_change_nothing():
+    wl = get_workload("tiny")
+    cfg, st, _ = make_pair(wl)
+    src = PageViewSource(wl)
+    g.gear_step(st, g.DeviceBatch.from_host(src.batch(0)), wl.M, wl.lr)
+    torch.cuda.synchronize()
+    before = [t.clone() for t in (st.user_emb, st.url_emb, st.mlp_params, st.grad_accum, st.counts)]
+    good = src.batch(1)
+    for field, value in (("user_id", wl.n_users), ("url_id", -1), ("img_id", wl.n_images), ("img_off", None)):
+        bad = PageViewBatch(*(getattr(good, f).copy() for f in ("user_id", "url_id", "img_off", "img_id", "label")))
+        if field == "img_off":
+            bad.img_off[10], bad.img_off[11] = bad.img_off[11], bad.img_off[10] - 1     # not monotone
+        else:
+            getattr(bad, field)[17] = value
+        g.gear_step(st, g.DeviceBatch.from_host(bad), wl.M, wl.lr)
+        torch.cuda.synchronize()
+        assert int(st.status.item()) == g.GEAR_ERR_RANGE, field
+        for a, b in zip(before, (st.user_emb, st.url_emb, st.mlp_params, st.grad_accum, st.counts)):
+            assert torch.equal(a, b), field
+    # the next good step clears the status and runs
+    g.gear_step(st, g.DeviceBatch.from_host(good), wl.M, wl.lr)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0 and not torch.equal(before[4], st.counts)
+
+
+def test_ready_list_over_capacity_is_reported_and_changes_nothing():
+    wl = get_workload("tiny").scaled(M=1)
+    cfg, st, _ = make_pair(wl, ready_cap=100)
+    before = [t.clone() for t in (st.user_emb, st.mlp_params, st.grad_accum, st.counts)]
+    g.gear_step(st, g.DeviceBatch.from_host(PageViewSource(wl).batch(0)), wl.M, wl.lr)   # nnz > 100 emissions
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == g.GEAR_ERR_CAPACITY
+    for a, b in zip(before, (st.user_emb, st.mlp_params, st.grad_accum, st.counts)):
+        assert torch.equal(a, b)
+
+
+def test_host_checked_arguments():
+    wl = get_workload("tiny")
+    cfg, st, _ = make_pair(wl)
+    dev = g.DeviceBatch.from_host(PageViewSource(wl).batch(0))
+    for M, lr in ((0, 0.1), (4, float("nan")), (4, float("inf"))):
+        with pytest.raises(g.GearError) as e:
+            g.gear_step(st, dev, M, lr)
+        assert e.value.code == g.GEAR_ERR_INVALID
+    big = g.DeviceBatch.from_host(PageViewSource(wl).batch(0, batch=wl.batch + 1))
+    with pytest.raises(g.GearError) as e:
+        g.gear_step(st, big, wl.M, wl.lr)
+    assert e.value.code == g.GEAR_ERR_INVALID
+    st.workspace = st.workspace[:1024]
+    with pytest.raises(g.GearError) as e:
+        g.gear_step(st, dev, wl.M, wl.lr)
+    assert e.value.code == g.GEAR_ERR_CAPACITY
+
+
+# ------------------------------------------------------------------ cache refresh
+def test_refresh_overwrites_rows_and_nothing_else():
+    wl = get_workload("tiny")
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    check_step(wl, st, orc, src.batch(0), wl.lr, "before refresh")
+    accum, counts = st.grad_accum.clone(), st.counts.clone()
+    ids = np.array([5, 1999, 0, 77], dtype=np.int32)
+    rows = np.random.default_rng(3).normal(0, 1, (4, wl.dfv_dim)).astype(np.float32)
+    old = st.dfv_cache.clone()
+    g.gear_refresh_dfv(st, torch.from_numpy(ids).cuda(), torch.from_numpy(rows).cuda())
+    orc.refresh_dfv(ids, rows)
+    torch.cuda.synchronize()
+    assert torch.equal(accum, st.grad_accum) and torch.equal(counts, st.counts)      # another table
+    assert np.array_equal(st.dfv_cache[torch.from_numpy(ids.astype(np.int64)).cuda()].cpu().numpy(), rows)
+    mask = torch.ones(wl.n_images, dtype=torch.bool, device="cuda")
+    mask[torch.from_numpy(ids.astype(np.int64)).cuda()] = False
+    assert torch.equal(old[mask], st.dfv_cache[mask])
+    check_step(wl, st, orc, src.batch(1), wl.lr, "after refresh")
+    check_state(wl, st, orc, "after refresh")
+    # whole-table refresh (image_ids = NULL) and an out-of-range id
+    full = torch.randn((wl.n_images, wl.dfv_dim), device="cuda")
+    g.gear_refresh_dfv(st, None, full)
+    g.gear_refresh_dfv(st, torch.tensor([3, wl.n_images], dtype=torch.int32, device="cuda"), full[:2] * 0)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == g.GEAR_ERR_RANGE
+    assert torch.equal(st.dfv_cache[4:], full[4:]) and not st.dfv_cache[3].any()
