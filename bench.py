@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Throughput of the Gear Training sparse-part step on one MI355X.
+
+A "step" is one gear_step over one batch of synthetic page views of the "large" workload
+(65,536 views, 50M users, 2^25 URL buckets, 4M images with 1024-wide bf16 DFVs, MLP
+1152-1024-256-1 on bf16 MFMA, M = 16), inputs resident in HBM.  The full DFV refresh the workload
+performs every 500 steps is timed separately and its amortised share is added to ms_per_step.
+
+Prints ONE JSON line: page-views/s, the roofline of the dominant kernel (its duration measured
+with HIP events on the launch stream), per-kernel figures, and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+BYTES = {"f32": 4, "bf16": 2}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--cpu-sample-views", type=int, default=32768,
+                    help="views of the oracle's timed sample (0 = skip the CPU baseline)")
+    return ap.parse_args()
+
+
+class WorkModel:
+    """Algorithmic flops / compulsory HBM bytes of each timed launch, from the batch itself."""
+
+    def __init__(self, wl, layers_in, layers_out):
+        self.wl, self.lin, self.lout = wl, layers_in, layers_out
+        self.counts = np.zeros(wl.n_images, dtype=np.int64)
+
+    def step(self, batch):
+        wl = self.wl
+        B, nnz, d, D, F = batch.B, batch.nnz, wl.emb_dim, wl.dfv_dim, wl.in_features
+        e_emb, e_dfv, e_act = BYTES[wl.emb_dtype], BYTES[wl.dfv_dtype], BYTES[wl.mlp_dtype]
+        uu, ul = len(np.unique(batch.user_id)), len(np.unique(batch.url_id))
+        img, n_i = np.unique(batch.img_id, return_counts=True)
+        p = self.counts[img] % wl.M
+        final = (p + n_i) % wl.M
+        emits = int(((p + n_i) // wl.M).sum())
+        self.counts[img] += n_i
+        with_img = int((np.diff(batch.img_off) > 0).sum())
+        work = {}
+        for l, (k, n) in enumerate(zip(self.lin, self.lout)):
+            if l == len(self.lin) - 1:
+                break
+            work[f"fwd_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)
+            work[f"dgrad_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)
+            work[f"wgrad_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)
+        work["gather_pool"] = ("hbm", 12.0 * B + 4.0 * nnz + (uu + ul) * d * e_emb + len(img) * D * e_dfv
+                               + B * F * e_act)
+        work["embedding_update"] = ("hbm", 16.0 * B + 2.0 * B * d * 4 + 2.0 * (uu + ul) * d * e_emb)
+        work["accumulate"] = ("hbm", 12.0 * nnz + with_img * D * 4.0 + int((p != 0).sum()) * D * 4.0
+                              + int(((final != 0) | (p != 0)).sum()) * D * 4.0 + emits * D * 4.0)
+        return work
+
+
+def source_hash():
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1806_03925_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(kernel):
+    """HBM bytes per launch from the rocprofv3 counter runs, if they were taken on this source."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    if rec.get("source_hash") != source_hash():
+        return None
+    return rec.get("kernels", {}).get(kernel)
+
+
+def cpu_baseline(wl, views):
+    """The oracle as it stands, timed on this host over `views` page views of step 0's batch."""
+    from threadpoolctl import threadpool_info
+
+    from gear_inputs import PageViewSource
+    from oracle.from_workload import oracle_for
+    orc = oracle_for(wl)
+    batch = PageViewSource(wl).batch(0, batch=views)
+    orc.user_emb.prefetch(batch.user_id)
+    orc.url_emb.prefetch(batch.url_id)
+    orc.dfv.prefetch(batch.img_id)
+    t0 = time.perf_counter()
+    orc.step(batch, float(np.float32(wl.lr)))
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": views / dt, "unit": "page-views/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 oracle step over the first {views} views of the {wl.name} workload's batch 0 "
+                      f"({dt:.1f} s; table rows materialised beforehand)"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+              "the step has no multi-GPU path", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1806_03925_amd as g
+    from gear_inputs import PageViewSource, get_workload
+
+    wl = get_workload(args.workload)
+    torch.cuda.set_device(0)
+    cfg = g.config_for(wl)
+    st = g.GearState(cfg)
+    g.gear_init_tables(st)
+    g.gear_fill_normal(st.dfv_cache, wl.n_images, wl.dfv_dim, wl.seed, 3, wl.dfv_std)
+    torch.cuda.synchronize()
+
+    K, W = args.steps, args.warmup
+    src = PageViewSource(wl)
+    pool = min(W + 2 * K, 160)
+    host = [src.batch(i) for i in range(pool)]
+    dev = [g.DeviceBatch.from_host(b) for b in host]
+    lr = float(wl.lr)
+    lin = [wl.in_features] + list(wl.layers[:-1])
+    model = WorkModel(wl, lin, list(wl.layers))
+
+    it = 0
+    for _ in range(W):
+        g.gear_step(st, dev[it % pool], wl.M, lr)
+        model.step(host[it % pool])
+        it += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        g.gear_step(st, dev[it % pool], wl.M, lr)
+        it += 1
+    torch.cuda.synchronize()
+    loop_ms = (time.perf_counter() - t0) * 1e3
+    for i in range(it - K, it):
+        model.step(host[i % pool])
+    assert int(st.status.item()) == 0 and np.isfinite(float(st.loss.item()))
+    loss = float(st.loss.item())
+
+    # per-kernel durations: the same steps again with HIP events around every launch
+    st.profile = g.GearProfile()
+    spans, work = {}, {}
+    for _ in range(K):
+        g.gear_step(st, dev[it % pool], wl.M, lr)
+        torch.cuda.synchronize()
+        for name, ms in st.profile.spans():
+            spans.setdefault(name, []).append(ms)
+        for name, (bound, amount) in model.step(host[it % pool]).items():
+            work.setdefault(name, [bound, 0.0])[1] += amount / K
+        it += 1
+    st.profile.close()
+    st.profile = None
+
+    # the workload's periodic full DFV refresh (new vectors stand in for a Dense-Part inference pass)
+    refresh_ms = 0.0
+    if wl.refresh_every:
+        fresh = torch.empty_like(st.dfv_cache)
+        g.gear_fill_normal(fresh, wl.n_images, wl.dfv_dim, wl.seed + 1, 3, wl.dfv_std)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        g.gear_refresh_dfv(st, None, fresh)
+        e1.record()
+        torch.cuda.synchronize()
+        refresh_ms = e0.elapsed_time(e1)
+        del fresh
+
+    ms_per_step = loop_ms / K + (refresh_ms / wl.refresh_every if wl.refresh_every else 0.0)
+    value = wl.batch / (ms_per_step * 1e-3)
+
+    kernels = []
+    for name, samples in spans.items():
+        launches = len(samples) / K
+        avg_ms = float(np.mean(samples))
+        row = {"name": name, "ms_per_step": avg_ms * launches, "launches_per_step": launches}
+        if name in work:
+            bound, amount = work[name]
+            if bound == "mfma":
+                row.update(bound="mfma", achieved=amount / (avg_ms * 1e-3) / 1e12, unit="TFLOP/s",
+                           peak=MFMA_PEAK_TFLOPS[wl.mlp_dtype])
+            else:
+                row.update(bound="hbm", achieved=amount / (avg_ms * 1e-3) / 1e9, unit="GB/s", peak=HBM_PEAK_GBS)
+            row["frac"] = row["achieved"] / row["peak"]
+            row["algorithmic_per_launch"] = amount
+        kernels.append(row)
+    kernels.sort(key=lambda r: -r["ms_per_step"])
+    dominant = next(r for r in kernels if "bound" in r)
+    roofline = {"kernel": dominant["name"], "bound": dominant["bound"], "achieved": dominant["achieved"],
+                "peak": dominant["peak"], "unit": dominant["unit"], "frac": dominant["frac"],
+                "avg_launch_ms": dominant["ms_per_step"] / dominant["launches_per_step"],
+                "traffic": recorded_traffic(dominant["name"])}
+
+    out = {
+        "metric": "page-views/sec per gear_step at 1 GPU", "value": value, "unit": "page-views/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.mlp_dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "n_users": wl.n_users, "n_urls": wl.n_urls,
+                   "n_images": wl.n_images, "emb_dim": wl.emb_dim, "dfv_dim": wl.dfv_dim,
+                   "mlp": [wl.in_features, *wl.layers], "M": wl.M, "zipf_s": wl.zipf_image,
+                   "refresh_every": wl.refresh_every, "refresh_ms": refresh_ms,
+                   "loop_ms_per_step": loop_ms / K, "profiled_ms_per_step": sum(r["ms_per_step"] for r in kernels)},
+        "loss": loss,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if args.cpu_sample_views > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_views)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -100,6 +100,10 @@ typedef struct gear_step_out {
    * [max_nnz], [1].  unique = distinct image ids ascending; segment s of the stable
    * permutation perm is perm[segoff[s] .. segoff[s+1]), flat CSR positions ascending. */
   int32_t *dbg_img_unique, *dbg_img_segoff, *dbg_img_perm, *dbg_n_img_unique;
+  /* Optional timing (NULL = off): a gear_profile from gear_profile_create.  Every kernel launch of
+   * the step is then bracketed by HIP events on `stream`; read them with gear_profile_span after
+   * synchronising the stream. */
+  void *profile;
 } gear_step_out;
 
 /* Bytes of scratch device memory gear_step needs for this configuration (0 on a bad config). */
@@ -162,6 +166,17 @@ gear_status gear_refresh_dfv(const gear_config *cfg, void *dfv_cache, const int3
 gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t n, int64_t key_range,
                            void *workspace, size_t workspace_bytes, int32_t *unique, int32_t *segoff,
                            int32_t *perm, int32_t *n_unique, void *stream);
+
+/* Per-kernel timing of a step, for benchmarks.  gear_profile_create allocates a fixed pool of HIP
+ * events on the current device (host memory; NULL on failure), gear_profile_destroy releases it.
+ * After a gear_step that was given the profile and after the stream has been synchronised,
+ * gear_profile_count returns the number of timed launches and gear_profile_span the name of
+ * launch i (a static string) and its duration in milliseconds. */
+typedef struct gear_profile gear_profile;
+gear_profile *gear_profile_create(void);
+void gear_profile_destroy(gear_profile *p);
+int32_t gear_profile_count(const gear_profile *p);
+gear_status gear_profile_span(const gear_profile *p, int32_t i, const char **name, float *ms);
 
 const char *gear_status_string(gear_status s);
 

@@ -24,6 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
     "gear_fill_normal", "gear_init_tables", "gear_step", "gear_refresh_dfv", "gear_group_ids",
+    "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
     "gear_status_string",
 )
 
@@ -50,7 +51,7 @@ class gear_step_out(C.Structure):
     _fields_ = [("loss", C.c_void_p), ("n_ready", C.c_void_p), ("ready_ids", C.c_void_p),
                 ("ready_grads", C.c_void_p), ("ready_cap", C.c_int32), ("status", C.c_void_p),
                 ("dbg_img_unique", C.c_void_p), ("dbg_img_segoff", C.c_void_p),
-                ("dbg_img_perm", C.c_void_p), ("dbg_n_img_unique", C.c_void_p)]
+                ("dbg_img_perm", C.c_void_p), ("dbg_n_img_unique", C.c_void_p), ("profile", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -81,6 +82,14 @@ def _load() -> C.CDLL:
     lib.gear_group_ids.restype = C.c_int
     lib.gear_group_ids.argtypes = [cfgp, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gear_profile_create.restype = C.c_void_p
+    lib.gear_profile_create.argtypes = []
+    lib.gear_profile_destroy.restype = None
+    lib.gear_profile_destroy.argtypes = [C.c_void_p]
+    lib.gear_profile_count.restype = C.c_int32
+    lib.gear_profile_count.argtypes = [C.c_void_p]
+    lib.gear_profile_span.restype = C.c_int
+    lib.gear_profile_span.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_float)]
     lib.gear_status_string.restype = C.c_char_p
     lib.gear_status_string.argtypes = [C.c_int]
     return lib
@@ -194,6 +203,7 @@ class GearState:
         self.status = torch.zeros(1, dtype=torch.int32, device=dev)
         self.ready_ids = torch.empty(max(self.ready_cap, 1), dtype=torch.int32, device=dev)
         self.ready_grads = torch.empty((max(self.ready_cap, 1), cfg.dfv_dim), dtype=torch.float32, device=dev)
+        self.profile = None          # a GearProfile to time every launch of the next steps
         self.dbg = None
         if debug:
             n = cfg.max_nnz
@@ -206,7 +216,8 @@ class GearState:
     def step_out(self) -> gear_step_out:
         d = self.dbg or (None, None, None, None)
         return gear_step_out(_ptr(self.loss), _ptr(self.n_ready), _ptr(self.ready_ids), _ptr(self.ready_grads),
-                             self.ready_cap, _ptr(self.status), _ptr(d[0]), _ptr(d[1]), _ptr(d[2]), _ptr(d[3]))
+                             self.ready_cap, _ptr(self.status), _ptr(d[0]), _ptr(d[1]), _ptr(d[2]), _ptr(d[3]),
+                             self.profile.handle if self.profile is not None else None)
 
     def layer_params(self, layer: int):
         """Views of W_l [out x in] and b_l [out] inside mlp_params."""
@@ -226,6 +237,29 @@ class GearState:
         if name == "dx":
             return raw.view(torch.float32)[:B * F].view(B, F)
         return raw.view(torch.float32)[:B]
+
+
+class GearProfile:
+    """HIP-event timing of every kernel launch of a step (gear_profile_* calls)."""
+
+    def __init__(self):
+        self.handle = lib.gear_profile_create()
+        if not self.handle:
+            raise GearError(GEAR_ERR_HIP, "gear_profile_create")
+
+    def spans(self):
+        """[(name, milliseconds)] of the last profiled step; the stream must have been synchronised."""
+        out = []
+        name, ms = C.c_char_p(), C.c_float()
+        for i in range(lib.gear_profile_count(self.handle)):
+            _check(lib.gear_profile_span(self.handle, i, C.byref(name), C.byref(ms)), "gear_profile_span")
+            out.append((name.value.decode(), float(ms.value)))
+        return out
+
+    def close(self):
+        if self.handle:
+            lib.gear_profile_destroy(self.handle)
+            self.handle = None
 
 
 def gear_init_tables(state: GearState) -> None:

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <new>
+
 namespace gear {
 
 namespace {
@@ -57,6 +59,37 @@ GroupProblem make_problem(const Layout &lay, char *ws, int slot, const int32_t *
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+}  // namespace gear
+
+// HIP-event pool for per-launch timing of a step
+struct gear_profile {
+  static constexpr int kMaxSpans = 96;
+  hipEvent_t start[kMaxSpans], stop[kMaxSpans];
+  const char *name[kMaxSpans];
+  int used;
+};
+
+namespace gear {
+namespace {
+
+struct Span {
+  gear_profile *p;
+  hipStream_t s;
+  int slot;
+  Span(gear_profile *prof, const char *name, hipStream_t stream) : p(prof), s(stream), slot(-1) {
+    if (p && p->used < gear_profile::kMaxSpans) {
+      slot = p->used++;
+      p->name[slot] = name;
+      (void)hipEventRecord(p->start[slot], s);
+    }
+  }
+  ~Span() {
+    if (slot >= 0) (void)hipEventRecord(p->stop[slot], s);
+  }
+};
 
 }  // namespace
 
@@ -150,9 +183,15 @@ bool make_layout(const gear_config &c, Layout *lay) {
 
 using namespace gear;
 
-#define GEAR_HIP(expr)                         \
-  do {                                         \
+#define GEAR_HIP(expr)                             \
+  do {                                             \
     if ((expr) != hipSuccess) return GEAR_ERR_HIP; \
+  } while (0)
+// a launch bracketed by profile events (when a profile is attached)
+#define GEAR_RUN(name, expr)    \
+  do {                          \
+    Span span_(prof, name, s);  \
+    GEAR_HIP(expr);             \
   } while (0)
 
 extern "C" {
@@ -245,10 +284,21 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   const int B = b->B, L = lay.L, F = lay.F, dt = cfg->mlp_dtype;
   int32_t *status = out->status;
 
-  GEAR_HIP(launch_begin(status, out->n_ready, out->loss, s));
+  gear_profile *prof = (gear_profile *)out->profile;
+  if (prof) prof->used = 0;
+  static const char *const kFwd[GEAR_MAX_LAYERS] = {"fwd_gemm_l0", "fwd_gemm_l1", "fwd_gemm_l2", "fwd_gemm_l3",
+                                                    "fwd_gemm_l4", "fwd_gemm_l5", "fwd_gemm_l6", "fwd_gemm_l7"};
+  static const char *const kDgrad[GEAR_MAX_LAYERS] = {"dgrad_gemm_l0", "dgrad_gemm_l1", "dgrad_gemm_l2",
+                                                      "dgrad_gemm_l3", "dgrad_gemm_l4", "dgrad_gemm_l5",
+                                                      "dgrad_gemm_l6", "dgrad_gemm_l7"};
+  static const char *const kWgrad[GEAR_MAX_LAYERS] = {"wgrad_gemm_l0", "wgrad_gemm_l1", "wgrad_gemm_l2",
+                                                      "wgrad_gemm_l3", "wgrad_gemm_l4", "wgrad_gemm_l5",
+                                                      "wgrad_gemm_l6", "wgrad_gemm_l7"};
+
+  GEAR_RUN("begin", launch_begin(status, out->n_ready, out->loss, s));
   if (B == 0) return GEAR_OK;
   int32_t *occ_view = (int32_t *)(ws + lay.occ_view);
-  GEAR_HIP(launch_validate(*cfg, *b, occ_view, status, s));
+  GEAR_RUN("validate", launch_validate(*cfg, *b, occ_view, status, s));
 
   // grouping of the three id lists and the plan of the per-image accumulation
   GroupBatch gb;
@@ -256,7 +306,7 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   gb.p[0] = make_problem(lay, ws, 0, b->user_id, B, cfg->n_users);
   gb.p[1] = make_problem(lay, ws, 1, b->url_id, B, cfg->n_urls);
   gb.p[2] = make_problem(lay, ws, 2, b->img_id, b->nnz, cfg->n_images);
-  GEAR_HIP(launch_group(gb, status, s));
+  GEAR_RUN("group_ids", launch_group(gb, status, s));
   AccumPlan plan;
   plan.tile_units = (int32_t *)(ws + lay.tile_units);
   plan.tile_emits = (int32_t *)(ws + lay.tile_emits);
@@ -264,19 +314,24 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   plan.unit_slot = (int32_t *)(ws + lay.unit_slot);
   plan.unit_seg = (int32_t *)(ws + lay.unit_seg);
   plan.n_units = (int32_t *)(ws + lay.n_units);
-  GEAR_HIP(launch_accum_plan(gb.p[2], plan, counts, M, out->ready_cap, out->n_ready, status, s));
+  GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, counts, M, out->ready_cap, out->n_ready, status, s));
 
   // forward
   void *x = ws + lay.x;
-  GEAR_HIP(launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
-  for (int l = 0; l < L; ++l)
-    GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt, ws + lay.wc[l],
-                                 ws + lay.wct[l], status, s));
+  GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
+  {
+    Span span_(prof, "cast_weights", s);
+    for (int l = 0; l < L; ++l)
+      GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt, ws + lay.wc[l],
+                                   ws + lay.wct[l], status, s));
+  }
   for (int l = 0; l < L - 1; ++l)
-    GEAR_HIP(launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l], lay.in_dim[l],
-                            EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr, ws + lay.h[l], status, s));
+    GEAR_RUN(kFwd[l], launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l],
+                                     lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
+                                     ws + lay.h[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
-  GEAR_HIP(launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1], b->label, B,
+  GEAR_RUN("logit_loss",
+           launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1], b->label, B,
                              lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial),
                              out->loss, status, s));
 
@@ -284,39 +339,43 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   float *dx = (float *)(ws + lay.dx);
   for (int l = L - 2; l >= 0; --l) {
     if (l > 0)
-      GEAR_HIP(launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l], EPI_MASK,
-                              nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1], status, s));
+      GEAR_RUN(kDgrad[l], launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l],
+                                         EPI_MASK, nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1], status, s));
     else
-      GEAR_HIP(launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_F32, nullptr, nullptr,
-                              dx, status, s));
+      GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_F32,
+                                         nullptr, nullptr, dx, status, s));
   }
 
   // SGD on the MLP: logit layer by weighted column sums, hidden layers by split-K wgrad
   float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
-  GEAR_HIP(launch_colsum_sgd(dt, ws + lay.h[L - 2], dz, B, lay.in_dim[L - 1], cpart, t->mlp_params + lay.w_off[L - 1],
-                             lr, status, s));
-  GEAR_HIP(launch_colsum_sgd(GEAR_F32, dz, nullptr, B, 1, cpart, t->mlp_params + lay.b_off[L - 1], lr, status, s));
+  {
+    Span span_(prof, "logit_layer_sgd", s);
+    GEAR_HIP(launch_colsum_sgd(dt, ws + lay.h[L - 2], dz, B, lay.in_dim[L - 1], cpart,
+                               t->mlp_params + lay.w_off[L - 1], lr, status, s));
+    GEAR_HIP(launch_colsum_sgd(GEAR_F32, dz, nullptr, B, 1, cpart, t->mlp_params + lay.b_off[L - 1], lr, status, s));
+  }
   for (int l = L - 2; l >= 0; --l) {
     const int splits = splitk_for(lay.out_dim[l], lay.in_dim[l], B);
-    GEAR_HIP(launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
-                                   lay.in_dim[l], B, splits, wpart, status, s));
-    GEAR_HIP(launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l], t->mlp_params + lay.w_off[l],
-                               lr, status, s));
-    GEAR_HIP(launch_colsum_sgd(dt, ws + lay.delta[l], nullptr, B, lay.out_dim[l], cpart, t->mlp_params + lay.b_off[l],
-                               lr, status, s));
+    GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
+                                              lay.in_dim[l], B, splits, wpart, status, s));
+    GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
+                                             t->mlp_params + lay.w_off[l], lr, status, s));
+    GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l], nullptr, B, lay.out_dim[l], cpart,
+                                           t->mlp_params + lay.b_off[l], lr, status, s));
   }
 
   // SGD on the touched embedding rows, then the per-image gradient bookkeeping
-  GEAR_HIP(launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb, lr, status, s));
-  GEAR_HIP(launch_accumulate(*cfg, gb.p[2], plan, occ_view, b->img_off, dx, F, grad_accum, counts, M, out->ready_ids,
-                             out->ready_grads, status, s));
-  GEAR_HIP(launch_count_update(gb.p[2], counts, status, s));
+  GEAR_RUN("embedding_update",
+           launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb, lr, status, s));
+  GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, occ_view, b->img_off, dx, F, grad_accum, counts, M,
+                                           out->ready_ids, out->ready_grads, status, s));
+  GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
 
-  if (out->dbg_img_unique)
+  if (out->dbg_img_unique && b->nnz > 0)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_unique, gb.p[2].unique, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_img_segoff)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_segoff, gb.p[2].segoff, ((size_t)b->nnz + 1) * 4, hipMemcpyDeviceToDevice, s));
-  if (out->dbg_img_perm)
+  if (out->dbg_img_perm && b->nnz > 0)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_perm, gb.p[2].perm, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_n_img_unique)
     GEAR_HIP(hipMemcpyAsync(out->dbg_n_img_unique, gb.p[2].n_unique, 4, hipMemcpyDeviceToDevice, s));
@@ -358,6 +417,38 @@ gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t 
   }
   GEAR_HIP(hipMemcpyAsync(segoff, gb.p[0].segoff, ((size_t)n + 1) * 4, hipMemcpyDeviceToDevice, s));
   GEAR_HIP(hipMemcpyAsync(n_unique, gb.p[0].n_unique, 4, hipMemcpyDeviceToDevice, s));
+  return GEAR_OK;
+}
+
+gear_profile *gear_profile_create(void) {
+  gear_profile *p = new (std::nothrow) gear_profile;
+  if (!p) return nullptr;
+  p->used = 0;
+  for (int i = 0; i < gear_profile::kMaxSpans; ++i) {
+    p->name[i] = "";
+    if (hipEventCreate(&p->start[i]) != hipSuccess || hipEventCreate(&p->stop[i]) != hipSuccess) {
+      delete p;  // events created so far are released with the context
+      return nullptr;
+    }
+  }
+  return p;
+}
+
+void gear_profile_destroy(gear_profile *p) {
+  if (!p) return;
+  for (int i = 0; i < gear_profile::kMaxSpans; ++i) {
+    (void)hipEventDestroy(p->start[i]);
+    (void)hipEventDestroy(p->stop[i]);
+  }
+  delete p;
+}
+
+int32_t gear_profile_count(const gear_profile *p) { return p ? p->used : 0; }
+
+gear_status gear_profile_span(const gear_profile *p, int32_t i, const char **name, float *ms) {
+  if (!p || !name || !ms || i < 0 || i >= p->used) return GEAR_ERR_INVALID;
+  *name = p->name[i];
+  GEAR_HIP(hipEventElapsedTime(ms, p->start[i], p->stop[i]));
   return GEAR_OK;
 }
 
