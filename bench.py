@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--cpu-sample-views", type=int, default=32768,
+    ap.add_argument("--cpu-sample-views", type=int, default=65536,
                     help="views of the oracle's timed sample (0 = skip the CPU baseline)")
     return ap.parse_args()
 

@@ -167,6 +167,19 @@ gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t 
                            void *workspace, size_t workspace_bytes, int32_t *unique, int32_t *segoff,
                            int32_t *perm, int32_t *n_unique, void *stream);
 
+/* The MLP's matrix products (Section 3, step 4: forward and back-propagation on the Sparse Part),
+ * exposed for tests.  All device memory, 16-byte aligned; accumulation is fp32.
+ *   form 0 (forward / dgrad): out[M x N] = A[M x K] * B[N x K]^T, operands of `dtype`, K and N
+ *     multiples of 8; epilogue 0: out(dtype) = max(acc + bias[n], 0); 1: out(dtype) = aux[m,n] > 0
+ *     ? acc : 0 with aux [M x N] of `dtype`; 2: out(f32) = acc.
+ *   form 1 (wgrad): out[M x N] (f32) = A[K x M]^T * B[K x N], M and N multiples of 8, contracted in
+ *     `splits` (1..64) ranges of K whose partial results (partial: [splits x M x N] f32) are added in
+ *     ascending order.
+ * status: device word, must be 0 on entry (a non-zero word makes the kernels return at once). */
+gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B, int32_t M, int32_t N, int32_t K,
+                      int32_t epilogue, const float *bias, const void *aux, void *out, int32_t splits,
+                      float *partial, int32_t *status, void *stream);
+
 /* Per-kernel timing of a step, for benchmarks.  gear_profile_create allocates a fixed pool of HIP
  * events on the current device (host memory; NULL on failure), gear_profile_destroy releases it.
  * After a gear_step that was given the profile and after the stream has been synchronised,

@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
     "gear_fill_normal", "gear_init_tables", "gear_step", "gear_refresh_dfv", "gear_group_ids",
-    "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
+    "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
     "gear_status_string",
 )
 
@@ -82,6 +82,10 @@ def _load() -> C.CDLL:
     lib.gear_group_ids.restype = C.c_int
     lib.gear_group_ids.argtypes = [cfgp, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gear_gemm.restype = C.c_int
+    lib.gear_gemm.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                              C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                              C.c_void_p]
     lib.gear_profile_create.restype = C.c_void_p
     lib.gear_profile_create.argtypes = []
     lib.gear_profile_destroy.restype = None
@@ -237,6 +241,28 @@ class GearState:
         if name == "dx":
             return raw.view(torch.float32)[:B * F].view(B, F)
         return raw.view(torch.float32)[:B]
+
+
+def gear_gemm(A: torch.Tensor, B: torch.Tensor, form: int, epilogue: int = 2, bias: Optional[torch.Tensor] = None,
+              aux: Optional[torch.Tensor] = None, splits: int = 1) -> torch.Tensor:
+    """form 0: A [M x K], B [N x K] -> A B^T (epilogue 0/1 in A's dtype, 2 in fp32);
+    form 1: A [K x M], B [K x N] -> A^T B in fp32, contracted in `splits` ranges of K."""
+    code = GEAR_BF16 if A.dtype == torch.bfloat16 else GEAR_F32
+    dev = A.device
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    if form == 0:
+        M, K = A.shape
+        N = B.shape[0]
+        out = torch.empty((M, N), dtype=torch.float32 if epilogue == 2 else A.dtype, device=dev)
+        partial = None
+    else:
+        K, M = A.shape
+        N = B.shape[1]
+        out = torch.empty((M, N), dtype=torch.float32, device=dev)
+        partial = torch.empty((splits, M, N), dtype=torch.float32, device=dev)
+    _check(lib.gear_gemm(code, form, _ptr(A), _ptr(B), M, N, K, epilogue, _ptr(bias), _ptr(aux), _ptr(out), splits,
+                         _ptr(partial), _ptr(status), _stream()), "gear_gemm")
+    return out
 
 
 class GearProfile:

@@ -18,16 +18,6 @@ size_t take(size_t *cursor, size_t bytes) {
   return at;
 }
 
-int splitk_for(int M, int N, int K) {
-  const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
-  int s = (768 + tiles - 1) / tiles;
-  int cap = K / 512;
-  if (cap < 1) cap = 1;
-  if (s > cap) s = cap;
-  if (s > 64) s = 64;
-  return s < 1 ? 1 : s;
-}
-
 int bits_for(int64_t range) {
   int b = 1;
   while (b < 31 && ((int64_t)1 << b) < range) ++b;
@@ -101,6 +91,7 @@ bool config_ok(const gear_config &c) {
   for (int l = 0; l < c.n_layers - 1; ++l)
     if (c.layer_out[l] < 8 || c.layer_out[l] % 8) return false;
   if (c.layer_out[c.n_layers - 1] != 1) return false;
+  if (c.layer_out[c.n_layers - 2] > 1024) return false;  // the logit kernel keeps a hidden row in one wavefront
   for (int dt : {c.emb_dtype, c.dfv_dtype, c.mlp_dtype})
     if (dt != GEAR_F32 && dt != GEAR_BF16) return false;
   if (c.max_batch < 1 || c.max_nnz < 1) return false;
@@ -139,7 +130,7 @@ bool make_layout(const gear_config &c, Layout *lay) {
     if (l < L - 1) {
       lay->h[l] = take(&cur, B * lay->out_dim[l] * ab);
       lay->delta[l] = take(&cur, B * lay->out_dim[l] * ab);
-      lay->splitk[l] = splitk_for(lay->out_dim[l], lay->in_dim[l], c.max_batch);
+      lay->splitk[l] = gemm_splitk_for(lay->out_dim[l], lay->in_dim[l], c.max_batch);
       const size_t pb = (size_t)lay->splitk[l] * wn * sizeof(float);
       if (pb > max_partial) max_partial = pb;
     }
@@ -148,10 +139,11 @@ bool make_layout(const gear_config &c, Layout *lay) {
   }
   lay->logits = take(&cur, B * sizeof(float));
   lay->dz = take(&cur, B * sizeof(float));
-  lay->loss_partial = take(&cur, kLossBlocks * sizeof(float));
+  lay->loss_partial = take(&cur, logit_partial_floats(lay->in_dim[L - 1]) * sizeof(float));
   lay->dx = take(&cur, B * F * sizeof(float));
   lay->wgrad_partial = take(&cur, max_partial);
   lay->colsum_partial = take(&cur, (size_t)lay->colsum_chunks * max_h * sizeof(float));
+  lay->emb_partial = take(&cur, embedding_partial_floats(c) * sizeof(float));
   lay->occ_view = take(&cur, NNZ * sizeof(int32_t));
   for (int s = 0; s < kMaxProblems; ++s) {
     const size_t n = s == 2 ? NNZ : B;
@@ -330,10 +322,10 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
                                      ws + lay.h[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
-  GEAR_RUN("logit_loss",
-           launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1], b->label, B,
-                             lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial),
-                             out->loss, status, s));
+  GEAR_RUN("logit_loss_sgd",
+           launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.w_off[L - 1],
+                             t->mlp_params + lay.b_off[L - 1], b->label, B, lay.in_dim[L - 1], logits, dz,
+                             ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial), out->loss, lr, status, s));
 
   // backward through the hidden layers down to dLoss/dx (all from the pre-step operand copies)
   float *dx = (float *)(ws + lay.dx);
@@ -346,27 +338,22 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
                                          nullptr, nullptr, dx, status, s));
   }
 
-  // SGD on the MLP: logit layer by weighted column sums, hidden layers by split-K wgrad
+  // SGD on the hidden layers: split-K wgrad and bias column sums (the logit layer was done above)
   float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
-  {
-    Span span_(prof, "logit_layer_sgd", s);
-    GEAR_HIP(launch_colsum_sgd(dt, ws + lay.h[L - 2], dz, B, lay.in_dim[L - 1], cpart,
-                               t->mlp_params + lay.w_off[L - 1], lr, status, s));
-    GEAR_HIP(launch_colsum_sgd(GEAR_F32, dz, nullptr, B, 1, cpart, t->mlp_params + lay.b_off[L - 1], lr, status, s));
-  }
   for (int l = L - 2; l >= 0; --l) {
-    const int splits = splitk_for(lay.out_dim[l], lay.in_dim[l], B);
+    const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
     GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
                                               lay.in_dim[l], B, splits, wpart, status, s));
     GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
                                              t->mlp_params + lay.w_off[l], lr, status, s));
-    GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l], nullptr, B, lay.out_dim[l], cpart,
+    GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l], B, lay.out_dim[l], cpart,
                                            t->mlp_params + lay.b_off[l], lr, status, s));
   }
 
   // SGD on the touched embedding rows, then the per-image gradient bookkeeping
   GEAR_RUN("embedding_update",
-           launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb, lr, status, s));
+           launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb,
+                                   (float *)(ws + lay.emb_partial), lr, status, s));
   GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, occ_view, b->img_off, dx, F, grad_accum, counts, M,
                                            out->ready_ids, out->ready_grads, status, s));
   GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
@@ -417,6 +404,30 @@ gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t 
   }
   GEAR_HIP(hipMemcpyAsync(segoff, gb.p[0].segoff, ((size_t)n + 1) * 4, hipMemcpyDeviceToDevice, s));
   GEAR_HIP(hipMemcpyAsync(n_unique, gb.p[0].n_unique, 4, hipMemcpyDeviceToDevice, s));
+  return GEAR_OK;
+}
+
+gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B, int32_t M, int32_t N, int32_t K,
+                      int32_t epilogue, const float *bias, const void *aux, void *out, int32_t splits,
+                      float *partial, int32_t *status, void *stream) {
+  if ((dtype != GEAR_F32 && dtype != GEAR_BF16) || !A || !B || !out || !status || M < 1 || N < 1 || K < 1)
+    return GEAR_ERR_INVALID;
+  const int vec = dtype == GEAR_BF16 ? 8 : 4;
+  if (!aligned16(A) || !aligned16(B) || !aligned16(out)) return GEAR_ERR_INVALID;
+  hipStream_t s = (hipStream_t)stream;
+  if (form == 0) {
+    if (K % vec || N % vec || epilogue < EPI_BIAS_RELU || epilogue > EPI_F32) return GEAR_ERR_INVALID;
+    if ((epilogue == EPI_BIAS_RELU && !bias) || (epilogue == EPI_MASK && (!aux || !aligned16(aux))))
+      return GEAR_ERR_INVALID;
+    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, status, s));
+  } else if (form == 1) {
+    if (M % vec || N % vec || splits < 1 || splits > 64 || !partial) return GEAR_ERR_INVALID;
+    GEAR_HIP(launch_gemm_tn_splitk(dtype, A, B, M, N, K, splits, partial, status, s));
+    GEAR_HIP(launch_fill_zero(out, (size_t)M * N * sizeof(float), s));
+    GEAR_HIP(launch_splitk_sgd(partial, splits, (int64_t)M * N, (float *)out, -1.0f, status, s));
+  } else {
+    return GEAR_ERR_INVALID;
+  }
   return GEAR_OK;
 }
 

@@ -117,7 +117,7 @@ struct Layout {
   size_t act_bytes;                  // sizeof(mlp_dtype)
 
   size_t x, h[GEAR_MAX_LAYERS], delta[GEAR_MAX_LAYERS], logits, dz, loss_partial, dx;
-  size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial;
+  size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial, emb_partial;
   size_t occ_view;
   struct G {
     size_t keys[2], vals[2], block_hist, tile_heads, unique, segoff, pos_seg, n_unique;
@@ -129,8 +129,8 @@ struct Layout {
 bool make_layout(const gear_config &cfg, Layout *lay);
 bool config_ok(const gear_config &cfg);
 
-constexpr int kColsumRows = 512;     // rows per partial of a column sum
-constexpr int kLossBlocks = 256;     // workgroups (and partial sums) of the loss kernel
+constexpr int kColsumRows = 128;     // rows per partial of a column sum
+constexpr int kLossBlocks = 2048;    // most workgroups (and partial sums) of the logit/loss kernel
 
 // ------------------------------------------------------------------------------------------------
 // kernel launchers (each defined next to its kernel)
@@ -164,19 +164,22 @@ hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N,
 // partial[z][M x N] = sum over the z-th K range of A[K x M]^T * B[K x N] (operands M-/N-contiguous).
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
                                  float *partial, const int32_t *status, hipStream_t s);
+int gemm_splitk_for(int M, int N, int K);  // wgrad split count for a [M x N] result contracted over K
 hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, float lr,
                              const int32_t *status, hipStream_t s);
 
-hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, const float *bias_last,
+hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
                              const float *label, int B, int H, float *logits, float *dz, void *delta,
-                             float *loss_partial, float *loss, const int32_t *status, hipStream_t s);
+                             float *partials, float *loss, float lr, const int32_t *status, hipStream_t s);
+size_t logit_partial_floats(int H);
 
-hipError_t launch_colsum_sgd(int dtype, const void *src, const float *row_weight, int B, int H,
-                             float *partial, float *dst, float lr, const int32_t *status, hipStream_t s);
+hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, float lr,
+                             const int32_t *status, hipStream_t s);
 
 hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
-                                   const float *dx, int F, void *user_emb, void *url_emb, float lr,
+                                   const float *dx, int F, void *user_emb, void *url_emb, float *partials, float lr,
                                    const int32_t *status, hipStream_t s);
+size_t embedding_partial_floats(const gear_config &cfg);
 
 hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan,
                              const int32_t *occ_view, const int32_t *img_off, const float *dx, int F,

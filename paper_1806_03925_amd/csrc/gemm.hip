@@ -5,13 +5,19 @@
 //   dgrad     d_{l-1}  = (d_l W_l) * [a_{l-1} > 0]     NT on the transposed weight copy
 //   wgrad     dW_l     = d_l^T h_{l-1}                  TN, split over the batch, fixed-order sum
 //
-// One workgroup = 4 wavefronts (2 x 2), block tile 128 x 128, each wavefront 64 x 64 as 2 x 2
-// MFMA 32x32 tiles.  bf16 operands use v_mfma_f32_32x32x16_bf16 (8 k-values per lane), fp32
-// operands v_mfma_f32_32x32x2_f32; accumulation is fp32 in both.  Operand tiles sit in LDS as
-// [row][k] with k contiguous, so a lane fetches its MFMA operand with one 16-byte LDS read.  For the
-// TN form the global tiles are [k][row]; each thread transposes an 8 x 8 block in registers on
-// the way into LDS.
+// One workgroup = 4 wavefronts (2 x 2) on a 256 x 128 block tile; a wavefront owns 128 x 64 as
+// 4 x 2 MFMA 32x32 tiles, so an operand fetched from LDS is used by two (A) or four (B) MFMAs.
+// bf16 operands use v_mfma_f32_32x32x16_bf16 (8 k-values per lane), fp32 operands
+// v_mfma_f32_32x32x2_f32; accumulation is fp32 in both.  Operand tiles sit in LDS as [row][k]
+// with k contiguous, so a lane fetches a bf16 MFMA operand with one 16-byte LDS read.  The next
+// k-tile is prefetched from global memory into registers while the current one is multiplied.
+// For the TN form the global tiles are [k][row]; a thread transposes 8 x 8 blocks in registers
+// on the way into LDS.  bf16 results leave through LDS so that every lane stores 16 contiguous
+// bytes.  Consecutive workgroup ids are spread over the eight XCDs by the hardware; the tile index
+// is remapped so that workgroups on one XCD walk neighbouring tiles and share operands in its L2.
 #include "gear_internal.hpp"
+
+#include <type_traits>
 
 namespace gear {
 namespace {
@@ -19,7 +25,10 @@ namespace {
 typedef __bf16 bf16x8_v __attribute__((ext_vector_type(8)));
 typedef float f32x16_v __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, THREADS = 256;
+constexpr int BM = 256, BN = 128, THREADS = 256;
+constexpr int WM = 128, WN = 64;           // wave tile
+constexpr int TM = WM / 32, TN = WN / 32;  // MFMA tiles per wave
+constexpr int kXcds = 8;
 
 template <typename T> struct Tile;
 template <> struct Tile<bf16_t> {
@@ -37,150 +46,180 @@ union Pack16 {
   float s[4];
 };
 
-// ---- global -> registers -----------------------------------------------------------------------
-// NT: tile rows are matrix rows, k contiguous.  rows x BK elements = rows*BK/VEC 16-byte vectors.
-template <typename T, int NV>
-__device__ __forceinline__ void load_nt(Pack16 (&r)[NV], const T *__restrict__ src, int ld, int row0, int rows_total,
-                                        int k0, int k_end, int tid) {
-  constexpr int VPR = Tile<T>::BK / Tile<T>::VEC;
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int v = tid + THREADS * i;
-    const int row = row0 + v / VPR, k = k0 + (v % VPR) * Tile<T>::VEC;
-    if (row < rows_total && k < k_end)
-      r[i].u = *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + k);
-    else
-      r[i].u = make_uint4(0u, 0u, 0u, 0u);
-  }
+// workgroup id -> tile id such that the workgroups of one XCD (ids congruent modulo 8) cover a
+// contiguous range of tiles
+__device__ __forceinline__ int xcd_remap(int bid, int n_blocks) {
+  const int per = n_blocks / kXcds, rem = n_blocks % kXcds;
+  const int xcd = bid % kXcds, local = bid / kXcds;
+  // the first `rem` XCDs own per + 1 tiles
+  const int start = xcd * per + (xcd < rem ? xcd : rem);
+  return start + local;
 }
 
-template <typename T, int NV>
-__device__ __forceinline__ void store_nt(const Pack16 (&r)[NV], T *lds, int tid) {
-  constexpr int VPR = Tile<T>::BK / Tile<T>::VEC;
-  constexpr int LDK = Tile<T>::LDK;
+// ---- global -> registers -> LDS, NT form: tile rows are matrix rows, k contiguous ------------------
+template <typename T, int ROWS>
+struct StageNT {
+  static constexpr int VPR = Tile<T>::BK / Tile<T>::VEC;  // 16-byte vectors per tile row
+  static constexpr int NV = ROWS * VPR / THREADS;
+  Pack16 r[NV];
+
+  __device__ __forceinline__ void load(const T *__restrict__ src, int ld, int row0, int rows_total, int k0, int k_end,
+                                       int tid) {
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int v = tid + THREADS * i;
-    const int row = v / VPR, kv = (v % VPR) * Tile<T>::VEC;
-    if constexpr (sizeof(T) == 2) {
-      *reinterpret_cast<uint4 *>(lds + row * LDK + kv) = r[i].u;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) lds[row * LDK + kv + e] = r[i].s[e];
+    for (int i = 0; i < NV; ++i) {
+      const int v = tid + THREADS * i;
+      const int row = row0 + v / VPR, k = k0 + (v % VPR) * Tile<T>::VEC;
+      if (row < rows_total && k < k_end)
+        r[i].u = *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + k);
+      else
+        r[i].u = make_uint4(0u, 0u, 0u, 0u);
     }
   }
-}
-
-// TN, bf16: a thread owns one 8(k) x 8(row) block: 8 vectors along `row`, one per k.
-__device__ __forceinline__ void load_tn_bf16(Pack16 (&r)[8], const bf16_t *__restrict__ src, int ld, int row0,
-                                             int rows_total, int k0, int k_end, int blk) {
-  // 128 rows = 16 row-vectors; 64 k = 8 k-blocks; blk in [0, 128)
-  const int rv = blk % 16, kb = blk / 16;
-  const int row = row0 + rv * 8;
+  __device__ __forceinline__ void store(T *lds, int tid) const {
+    constexpr int LDK = Tile<T>::LDK;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int k = k0 + kb * 8 + e;
-    if (row < rows_total && k < k_end)
-      r[e].u = *reinterpret_cast<const uint4 *>(src + (size_t)k * ld + row);
-    else
-      r[e].u = make_uint4(0u, 0u, 0u, 0u);
-  }
-}
-
-__device__ __forceinline__ void store_tn_bf16(const Pack16 (&r)[8], bf16_t *lds, int blk) {
-  constexpr int LDK = Tile<bf16_t>::LDK;
-  const int rv = blk % 16, kb = blk / 16;
+    for (int i = 0; i < NV; ++i) {
+      const int v = tid + THREADS * i;
+      const int row = v / VPR, kv = (v % VPR) * Tile<T>::VEC;
+      if constexpr (sizeof(T) == 2) {
+        *reinterpret_cast<uint4 *>(lds + row * LDK + kv) = r[i].u;
+      } else {
 #pragma unroll
-  for (int m = 0; m < 8; ++m) {  // output row m of the block: k = 0..7 from r[k].elem[m]
-    Pack16 o;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t a = r[2 * j].w[m >> 1], b = r[2 * j + 1].w[m >> 1];
-      o.w[j] = (m & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0x0000ffffu) | (b << 16));
+        for (int e = 0; e < 4; ++e) lds[row * LDK + kv + e] = r[i].s[e];
+      }
     }
-    *reinterpret_cast<uint4 *>(lds + (rv * 8 + m) * LDK + kb * 8) = o.u;
   }
-}
+};
 
-// TN, fp32: tile is 16(k) x 128(row) floats = 512 float4 along `row`; 2 per thread.
-__device__ __forceinline__ void load_tn_f32(Pack16 (&r)[2], const float *__restrict__ src, int ld, int row0,
-                                            int rows_total, int k0, int k_end, int tid) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int v = tid + THREADS * i;
-    const int k = k0 + v / 32, row = row0 + (v % 32) * 4;
-    if (row < rows_total && k < k_end)
-      r[i].u = *reinterpret_cast<const uint4 *>(src + (size_t)k * ld + row);
-    else
-      r[i].u = make_uint4(0u, 0u, 0u, 0u);
-  }
-}
+// ---- TN form, bf16: the global tile is [64 k][ROWS], a thread owns 8(k) x 8(row) blocks ------------
+template <int ROWS>
+struct StageTNbf16 {
+  static constexpr int BLOCKS = (ROWS / 8) * 8;                       // 8 k-blocks
+  static constexpr int NB = (BLOCKS + THREADS - 1) / THREADS;         // blocks per thread (1)
+  Pack16 r[NB][8];
 
-__device__ __forceinline__ void store_tn_f32(const Pack16 (&r)[2], float *lds, int tid) {
-  constexpr int LDK = Tile<float>::LDK;
+  __device__ __forceinline__ void load(const bf16_t *__restrict__ src, int ld, int row0, int rows_total, int k0,
+                                       int k_end, int tid) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int v = tid + THREADS * i;
-    const int k = v / 32, row = (v % 32) * 4;
+    for (int b = 0; b < NB; ++b) {
+      const int blk = tid + THREADS * b;
+      const int rv = blk % (ROWS / 8), kb = blk / (ROWS / 8);
+      const int row = row0 + rv * 8;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) lds[(row + e) * LDK + k] = r[i].s[e];
+      for (int e = 0; e < 8; ++e) {
+        const int k = k0 + kb * 8 + e;
+        if (blk < BLOCKS && row < rows_total && k < k_end)
+          r[b][e].u = *reinterpret_cast<const uint4 *>(src + (size_t)k * ld + row);
+        else
+          r[b][e].u = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
   }
-}
+  __device__ __forceinline__ void store(bf16_t *lds, int tid) const {
+    constexpr int LDK = Tile<bf16_t>::LDK;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int blk = tid + THREADS * b;
+      if (blk >= BLOCKS) continue;
+      const int rv = blk % (ROWS / 8), kb = blk / (ROWS / 8);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {  // row m of the block collects element m of the eight k-vectors
+        Pack16 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t a = r[b][2 * j].w[m >> 1], c = r[b][2 * j + 1].w[m >> 1];
+          o.w[j] = (m & 1) ? ((a >> 16) | (c & 0xffff0000u)) : ((a & 0x0000ffffu) | (c << 16));
+        }
+        *reinterpret_cast<uint4 *>(lds + (rv * 8 + m) * LDK + kb * 8) = o.u;
+      }
+    }
+  }
+};
+
+// ---- TN form, fp32: the global tile is [16 k][ROWS] floats = ROWS*4 float4 along `row` -------------
+template <int ROWS>
+struct StageTNf32 {
+  static constexpr int NV = ROWS * 4 / THREADS;
+  Pack16 r[NV];
+  __device__ __forceinline__ void load(const float *__restrict__ src, int ld, int row0, int rows_total, int k0,
+                                       int k_end, int tid) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int v = tid + THREADS * i;
+      const int k = k0 + v / (ROWS / 4), row = row0 + (v % (ROWS / 4)) * 4;
+      if (row < rows_total && k < k_end)
+        r[i].u = *reinterpret_cast<const uint4 *>(src + (size_t)k * ld + row);
+      else
+        r[i].u = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+  __device__ __forceinline__ void store(float *lds, int tid) const {
+    constexpr int LDK = Tile<float>::LDK;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int v = tid + THREADS * i;
+      const int k = v / (ROWS / 4), row = (v % (ROWS / 4)) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) lds[(row + e) * LDK + k] = r[i].s[e];
+    }
+  }
+};
 
 // ---- LDS -> MFMA -----------------------------------------------------------------------------------
 template <typename T>
-__device__ __forceinline__ void mma_tile(f32x16_v (&acc)[2][2], const T *As, const T *Bs, int wm, int wn, int lane) {
+__device__ __forceinline__ void mma_tile(f32x16_v (&acc)[TM][TN], const T *As, const T *Bs, int wm, int wn, int lane) {
   constexpr int LDK = Tile<T>::LDK, BK = Tile<T>::BK;
   const int r = lane & 31, g = lane >> 5;
   if constexpr (sizeof(T) == 2) {
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      Pack16 a[2], b[2];
+      Pack16 a[TM], b[TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i].u = *reinterpret_cast<const uint4 *>(As + (wm * 64 + i * 32 + r) * LDK + kk * 16 + g * 8);
-        b[i].u = *reinterpret_cast<const uint4 *>(Bs + (wn * 64 + i * 32 + r) * LDK + kk * 16 + g * 8);
-      }
+      for (int i = 0; i < TM; ++i)
+        a[i].u = *reinterpret_cast<const uint4 *>(As + (wm * WM + i * 32 + r) * LDK + kk * 16 + g * 8);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < TN; ++j)
+        b[j].u = *reinterpret_cast<const uint4 *>(Bs + (wn * WN + j * 32 + r) * LDK + kk * 16 + g * 8);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].b, b[j].b, acc[i][j], 0, 0, 0);
     }
   } else {
 #pragma unroll
     for (int kk = 0; kk < BK / 2; ++kk) {
-      float a[2], b[2];
+      float a[TM], b[TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i] = As[(wm * 64 + i * 32 + r) * LDK + kk * 2 + g];
-        b[i] = Bs[(wn * 64 + i * 32 + r) * LDK + kk * 2 + g];
-      }
+      for (int i = 0; i < TM; ++i) a[i] = As[(wm * WM + i * 32 + r) * LDK + kk * 2 + g];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < TN; ++j) b[j] = Bs[(wn * WN + j * 32 + r) * LDK + kk * 2 + g];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   }
 }
 
 // Accumulator element e of a 32x32 tile sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+// fp32 results are stored straight from that layout (a half-wave covers 128 contiguous bytes).
 template <typename T, int EPI>
-__device__ __forceinline__ void epilogue(const f32x16_v (&acc)[2][2], int m0, int n0, int wm, int wn, int lane, int M,
-                                         int N, const float *__restrict__ bias, const T *__restrict__ aux,
-                                         void *__restrict__ out) {
+__device__ __forceinline__ void epilogue_direct(const f32x16_v (&acc)[TM][TN], int m0, int n0, int wm, int wn,
+                                                int lane, int M, int N, const float *__restrict__ bias,
+                                                const T *__restrict__ aux, void *__restrict__ out) {
   const int c = lane & 31, g = lane >> 5;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + c;
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn * WN + j * 32 + c;
       if (n >= N) continue;
       float bn = 0.0f;
       if constexpr (EPI == EPI_BIAS_RELU) bn = bias[n];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+        const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
         if (m >= M) continue;
         const size_t idx = (size_t)m * N + n;
         float v = acc[i][j][e];
@@ -196,45 +235,481 @@ __device__ __forceinline__ void epilogue(const f32x16_v (&acc)[2][2], int m0, in
     }
 }
 
+// bf16 results: each wave parks 64 rows x 64 columns at a time in its own LDS patch, then every lane
+// moves 16 contiguous bytes (eight lanes per 128-byte row piece); the ReLU mask of the dgrad is read
+// with the same 16-byte pattern.
+template <int EPI>
+__device__ __forceinline__ void epilogue_bf16(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
+                                              int wn, int lane, int M, int N, const float *__restrict__ bias,
+                                              const bf16_t *__restrict__ aux, bf16_t *__restrict__ out) {
+  constexpr int LDC = WN + 8;  // bf16 elements per patch row
+  const int c = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int half = 0; half < TM / 2; ++half) {
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int i = half * 2 + ii;
+        const int n = n0 + wn * WN + j * 32 + c;
+        float bn = 0.0f;
+        if constexpr (EPI == EPI_BIAS_RELU) bn = n < N ? bias[n] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float v = acc[i][j][e];
+          if constexpr (EPI == EPI_BIAS_RELU) {
+            v += bn;
+            v = v > 0.0f ? v : 0.0f;
+          }
+          patch[(ii * 32 + 8 * (e / 4) + 4 * g + (e % 4)) * LDC + j * 32 + c] = f32_to_bf16(v);
+        }
+      }
+    // the patch is private to this wave: no workgroup barrier needed, only the wave's own LDS order
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = it * 8 + (lane >> 3), cv = (lane & 7) * 8;
+      const int m = m0 + wm * WM + half * 64 + row, n = n0 + wn * WN + cv;
+      if (m < M && n < N) {
+        Pack16 v;
+        v.u = *reinterpret_cast<const uint4 *>(patch + row * LDC + cv);
+        const size_t idx = (size_t)m * N + n;
+        if constexpr (EPI == EPI_MASK) {
+          Pack16 h;
+          h.u = *reinterpret_cast<const uint4 *>(aux + idx);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            // keep a half-word where the forward activation was positive (bf16 > 0: sign clear, not zero)
+            const uint32_t lo = h.w[w] & 0xffffu, hi = h.w[w] >> 16;
+            uint32_t keep = 0u;
+            if (lo != 0u && lo < 0x8000u) keep |= 0x0000ffffu;
+            if (hi != 0u && hi < 0x8000u) keep |= 0xffff0000u;
+            v.w[w] &= keep;
+          }
+        }
+        *reinterpret_cast<uint4 *>(out + idx) = v.u;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+
+// ---- NT form, bf16, K % 32 == 0: global -> LDS by DMA, four stages, 256 x 256 tile, 8 waves ---------
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+constexpr int DK = 32;                      // k-depth of a stage
+constexpr int DM = 256, DN = 256, DTHREADS = 512;
+constexpr int A_ELEMS = DM * DK, B_ELEMS = DN * DK;
+
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+
+template <int N> __device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+struct DmaPlan {
+  size_t a_off[2], b_off[2];  // element offsets of this lane's 16-byte pieces at k0 = 0
+};
+
+__device__ __forceinline__ void dma_tile(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const DmaPlan &p,
+                                         int k0, bf16_t *As, bf16_t *Bs, int wave) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    __builtin_amdgcn_global_load_lds((const void *)(A + p.a_off[i] + k0), (lds_ptr_t)(As + (i * 8 + wave) * 512), 16, 0,
+                                     0);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + k0), (lds_ptr_t)(Bs + (i * 8 + wave) * 512), 16, 0,
+                                     0);
+}
+
+// MFMA operands are fetched with explicit ds_read_b128 so that the only waits on the LDS path are
+// the ones written here (the compiler would otherwise make every LDS read wait for all DMA in flight).
+typedef uint32_t u32x4_v __attribute__((ext_vector_type(4)));
+#define LDS_READ16(dst, addr, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(dst) : "v"(addr) : "memory")
+#define MFMA_BF16(acc_, a_, b_) \
+  acc_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_v, a_), __builtin_bit_cast(bf16x8_v, b_), acc_, 0, 0, 0)
+
+__device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_addr0, uint32_t a_addr1, uint32_t b_addr0,
+                                          uint32_t b_addr1) {
+  u32x4_v p0, p1, p2, p3, q0, q1;   // k-step 0: A rows of the four m-tiles, B rows of the two n-tiles
+  u32x4_v r0, r1, r2, r3, s0, s1;   // k-step 1
+  LDS_READ16(p0, a_addr0, 0);
+  LDS_READ16(p1, a_addr0, 2048);
+  LDS_READ16(p2, a_addr0, 4096);
+  LDS_READ16(p3, a_addr0, 6144);
+  LDS_READ16(q0, b_addr0, 0);
+  LDS_READ16(q1, b_addr0, 2048);
+  LDS_READ16(r0, a_addr1, 0);
+  LDS_READ16(r1, a_addr1, 2048);
+  LDS_READ16(r2, a_addr1, 4096);
+  LDS_READ16(r3, a_addr1, 6144);
+  LDS_READ16(s0, b_addr1, 0);
+  LDS_READ16(s1, b_addr1, 2048);
+  asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3), "+v"(q0), "+v"(q1)::"memory");
+  MFMA_BF16(acc[0][0], p0, q0);
+  MFMA_BF16(acc[0][1], p0, q1);
+  MFMA_BF16(acc[1][0], p1, q0);
+  MFMA_BF16(acc[1][1], p1, q1);
+  MFMA_BF16(acc[2][0], p2, q0);
+  MFMA_BF16(acc[2][1], p2, q1);
+  MFMA_BF16(acc[3][0], p3, q0);
+  MFMA_BF16(acc[3][1], p3, q1);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3), "+v"(s0), "+v"(s1)::"memory");
+  MFMA_BF16(acc[0][0], r0, s0);
+  MFMA_BF16(acc[0][1], r0, s1);
+  MFMA_BF16(acc[1][0], r1, s0);
+  MFMA_BF16(acc[1][1], r1, s1);
+  MFMA_BF16(acc[2][0], r2, s0);
+  MFMA_BF16(acc[2][1], r2, s1);
+  MFMA_BF16(acc[3][0], r3, s0);
+  MFMA_BF16(acc[3][1], r3, s1);
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
+                                               int wn, int lane, int M, int N, const float *__restrict__ bias,
+                                               const bf16_t *__restrict__ aux, void *__restrict__ out) {
+  const int c = lane & 31, g = lane >> 5;
+  float bn[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn * WN + j * 32 + c;
+    bn[j] = (EPI == EPI_BIAS_RELU && n < N) ? bias[n] : 0.0f;
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    if constexpr (EPI == EPI_F32) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + c;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+          if (m < M && n < N) static_cast<float *>(out)[(size_t)m * N + n] = acc[i][j][e];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float v = acc[i][j][e];
+          if constexpr (EPI == EPI_BIAS_RELU) {
+            v += bn[j];
+            v = v > 0.0f ? v : 0.0f;
+          }
+          patch[(8 * (e / 4) + 4 * g + (e % 4)) * WN + j * 32 + c] = f32_to_bf16(v);
+        }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = it * 8 + (lane >> 3), cv = (lane & 7) * 8;
+        const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + cv;
+        Pack16 v;
+        v.u = *reinterpret_cast<const uint4 *>(patch + row * WN + cv);
+        if (m < M && n < N) {
+          const size_t idx = (size_t)m * N + n;
+          if constexpr (EPI == EPI_MASK) {
+            Pack16 h;
+            h.u = *reinterpret_cast<const uint4 *>(aux + idx);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const uint32_t lo = h.w[w] & 0xffffu, hi = h.w[w] >> 16;
+              uint32_t keep = 0u;
+              if (lo != 0u && lo < 0x8000u) keep |= 0x0000ffffu;
+              if (hi != 0u && hi < 0x8000u) keep |= 0xffff0000u;
+              v.w[w] &= keep;
+            }
+          }
+          *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(out) + idx) = v.u;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+constexpr int STAGES = 4;
+constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
+
+template <int EPI>
+__global__ void __launch_bounds__(DTHREADS)
+k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K,
+              const float *__restrict__ bias, const bf16_t *__restrict__ aux, void *__restrict__ out,
+              const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[STAGES * STAGE_ELEMS];   // [stage][A tile | B tile]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int n_tiles = (N + DN - 1) / DN;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / n_tiles) * DM, n0 = (tile % n_tiles) * DN;
+
+  DmaPlan plan;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = (i * 8 + wave) * 16 + (lane >> 2);
+    const int kv = (lane & 3) ^ swz(row);
+    plan.a_off[i] = (size_t)min(m0 + row, M - 1) * K + kv * 8;
+    plan.b_off[i] = (size_t)min(n0 + row, N - 1) * K + kv * 8;
+  }
+  // byte offsets, inside a stage, of this lane's MFMA operands for the two k-steps
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  uint32_t a_rel[2], b_rel[2];
+  {
+    const int r = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int off = r * DK + (((2 * kk + g) ^ swz(r)) * 8);
+      a_rel[kk] = lds_base + 2u * (uint32_t)(wm * WM * DK + off);
+      b_rel[kk] = lds_base + 2u * (uint32_t)(A_ELEMS + wn * WN * DK + off);
+    }
+  }
+
+  f32x16_v acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int nk = K / DK;
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < nk) dma_tile(A, B, plan, p * DK, lds + p * STAGE_ELEMS, lds + p * STAGE_ELEMS + A_ELEMS, wave);
+
+  // tile t is consumed from stage t % 4 while tiles t+1 and t+2 are in flight and t+3 is issued
+  int stage = 0;
+  for (int t = 0; t < nk; ++t) {
+    if (t + 2 < nk)
+      wait_vm<8>();
+    else if (t + 1 < nk)
+      wait_vm<4>();
+    else
+      wait_vm<0>();
+    block_barrier();
+    if (t + 3 < nk) {
+      const int ns = (stage + 3) & 3;
+      dma_tile(A, B, plan, (t + 3) * DK, lds + ns * STAGE_ELEMS, lds + ns * STAGE_ELEMS + A_ELEMS, wave);
+    }
+    const uint32_t so = (uint32_t)stage * (2u * STAGE_ELEMS);
+    mma_stage(acc, a_rel[0] + so, a_rel[1] + so, b_rel[0] + so, b_rel[1] + so);
+    stage = (stage + 1) & 3;
+  }
+  wait_vm<0>();
+  block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
+  bf16_t *patch = lds + wave * 32 * WN;
+  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out);
+}
+
+// ---- TN form (wgrad), bf16, by DMA and LDS transpose reads ---------------------------------------
+// Global tiles are [k][row] with `row` contiguous, which is also how they are kept in LDS: a DMA
+// instruction copies two k-rows of 256 values (1 KB).  The MFMA operand (8 k-values of one row per
+// lane) is assembled by ds_read_b64_tr_b16: sixteen lanes hand in the addresses of a 4(k) x 16(row)
+// block as four-value pieces and each lane gets back one row's four k-values.  Both operands use
+// the same pattern, so they agree on which k sits in which slot.
+typedef uint32_t u32x2_v __attribute__((ext_vector_type(2)));
+constexpr int TCHUNK = 1024 + 32;                 // bytes: two k-rows of 512 B, then a pad
+constexpr int TSTAGE = 2 * 16 * TCHUNK;           // A chunks then B chunks
+#define LDS_READ_TR(dst, addr, OFF) \
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(OFF) : "memory")
+
+struct TnPlan {
+  size_t a_off[2], b_off[2];
+};
+
+__device__ __forceinline__ void dma_tile_tn(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
+                                            const TnPlan &p, int k0, int M, int N, unsigned char *stage, int wave) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    __builtin_amdgcn_global_load_lds((const void *)(A + p.a_off[i] + (size_t)k0 * M),
+                                     (lds_ptr_t)(stage + (i * 8 + wave) * TCHUNK), 16, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + (size_t)k0 * N),
+                                     (lds_ptr_t)(stage + (16 + i * 8 + wave) * TCHUNK), 16, 0, 0);
+}
+
+// operand of MFMA tile at immediate OFF (bytes) for k-step KK: two transpose reads, k-rows +0..3 and +4..7
+#define TN_OPERAND(dst, base, OFF, KK)                                   \
+  {                                                                      \
+    u32x2_v lo_, hi_;                                                    \
+    LDS_READ_TR(lo_, base, (KK) * 8 * TCHUNK + (OFF));                   \
+    LDS_READ_TR(hi_, base, (KK) * 8 * TCHUNK + 2 * TCHUNK + (OFF));      \
+    dst = u32x4_v{lo_.x, lo_.y, hi_.x, hi_.y};                           \
+  }
+
+__device__ __forceinline__ void mma_stage_tn(f32x16_v (&acc)[TM][TN], uint32_t a_even, uint32_t a_odd, uint32_t b_even,
+                                             uint32_t b_odd) {
+#define TN_KSTEP(KK)                                       \
+  {                                                        \
+    u32x4_v p0, p1, p2, p3, q0, q1;                        \
+    TN_OPERAND(p0, a_even, 0, KK)                          \
+    TN_OPERAND(p1, a_odd, 64, KK)                          \
+    TN_OPERAND(p2, a_even, 128, KK)                        \
+    TN_OPERAND(p3, a_odd, 192, KK)                         \
+    TN_OPERAND(q0, b_even, 0, KK)                          \
+    TN_OPERAND(q1, b_odd, 64, KK)                          \
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3), "+v"(q0), "+v"(q1)::"memory"); \
+    MFMA_BF16(acc[0][0], p0, q0);                          \
+    MFMA_BF16(acc[0][1], p0, q1);                          \
+    MFMA_BF16(acc[1][0], p1, q0);                          \
+    MFMA_BF16(acc[1][1], p1, q1);                          \
+    MFMA_BF16(acc[2][0], p2, q0);                          \
+    MFMA_BF16(acc[2][1], p2, q1);                          \
+    MFMA_BF16(acc[3][0], p3, q0);                          \
+    MFMA_BF16(acc[3][1], p3, q1);                          \
+  }
+  TN_KSTEP(0)
+  TN_KSTEP(1)
+#undef TN_KSTEP
+}
+
+__global__ void __launch_bounds__(DTHREADS)
+k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K, int k_chunk,
+              float *__restrict__ partial, const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * TSTAGE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int n_tiles = (N + DN - 1) / DN;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / n_tiles) * DM, n0 = (tile % n_tiles) * DN;
+  const int k_begin = blockIdx.z * k_chunk;
+  const int k_end = min(K, k_begin + k_chunk);
+
+  // DMA: chunk c = k-rows 2c, 2c+1; lane p holds LDS slot p%32 of k-row p/32, which receives the
+  // 8-value piece (p%32) ^ (4 * (p/32)) so that odd k-rows sit 64 bytes away from even ones
+  TnPlan plan;
+  {
+    const int krow = lane >> 5, piece = (lane & 31) ^ (4 * krow);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int k = 2 * (i * 8 + wave) + krow;
+      const int ma = min(m0 + piece * 8, M - 8), nb = min(n0 + piece * 8, N - 8);  // stay inside the row
+      plan.a_off[i] = (size_t)k * M + ma;
+      plan.b_off[i] = (size_t)k * N + nb;
+    }
+  }
+  // transpose reads: lane l -> j = l%16, half = (l/16)%2 (rows +16), g = l/32 (k-rows +8);
+  // it addresses k-row 8 g + j/4 (+4 for the second read), rows 16 half + 4 (j%4) .. +3
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  uint32_t a_even, a_odd, b_even, b_odd;
+  {
+    const int j = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+    const int k = 8 * g + (j >> 2);
+    const int odd = k & 1;
+    const uint32_t row_off = (uint32_t)(k >> 1) * TCHUNK + (uint32_t)odd * 512u;
+    const uint32_t ca = 2u * (uint32_t)(wm * WM + 16 * half + 4 * (j & 3));
+    const uint32_t cb = 2u * (uint32_t)(wn * WN + 16 * half + 4 * (j & 3));
+    // odd k-rows are stored with the 64-byte halves of every 128 bytes swapped
+    a_even = lds_base + row_off + ca + (odd ? 64u : 0u);
+    a_odd = lds_base + row_off + ca - (odd ? 64u : 0u);
+    b_even = lds_base + 16u * TCHUNK + row_off + cb + (odd ? 64u : 0u);
+    b_odd = lds_base + 16u * TCHUNK + row_off + cb - (odd ? 64u : 0u);
+  }
+
+  f32x16_v acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int nk = (k_end - k_begin + DK - 1) / DK;   // k_end - k_begin is a multiple of DK (checked by the host)
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < nk) dma_tile_tn(A, B, plan, k_begin + p * DK, M, N, lds + p * TSTAGE, wave);
+
+  int stage = 0;
+  for (int t = 0; t < nk; ++t) {
+    if (t + 2 < nk)
+      wait_vm<8>();
+    else if (t + 1 < nk)
+      wait_vm<4>();
+    else
+      wait_vm<0>();
+    block_barrier();
+    if (t + 3 < nk) dma_tile_tn(A, B, plan, k_begin + (t + 3) * DK, M, N, lds + ((stage + 3) & 3) * TSTAGE, wave);
+    const uint32_t so = (uint32_t)stage * TSTAGE;
+    mma_stage_tn(acc, a_even + so, a_odd + so, b_even + so, b_odd + so);
+    stage = (stage + 1) & 3;
+  }
+  // fp32 partial of this k range
+  float *dst = partial + (size_t)blockIdx.z * M * N;
+  const int c = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn * WN + j * 32 + c;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+        if (m < M && n < N) dst[(size_t)m * N + n] = acc[i][j][e];
+      }
+    }
+}
+
 // ---- kernels ---------------------------------------------------------------------------------------
+constexpr size_t lds_bytes(size_t elem, int ldk) { return (size_t)(BM + BN) * ldk * elem; }
+
 template <typename T, int EPI>
 __global__ void __launch_bounds__(THREADS)
 k_gemm_nt(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K, const float *__restrict__ bias,
           const T *__restrict__ aux, void *__restrict__ out, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   constexpr int BK = Tile<T>::BK, LDK = Tile<T>::LDK;
-  constexpr int NV = BM * (BK / Tile<T>::VEC) / THREADS;
-  __shared__ __attribute__((aligned(16))) T As[BM * LDK];
-  __shared__ __attribute__((aligned(16))) T Bs[BN * LDK];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *As = reinterpret_cast<T *>(smem);
+  T *Bs = As + BM * LDK;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int n_tiles = (N + BN - 1) / BN;
-  const int m0 = (blockIdx.x / n_tiles) * BM, n0 = (blockIdx.x % n_tiles) * BN;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / n_tiles) * BM, n0 = (tile % n_tiles) * BN;
 
-  f32x16_v acc[2][2];
+  f32x16_v acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  Pack16 ra[NV], rb[NV];
-  load_nt<T, NV>(ra, A, K, m0, M, 0, K, tid);
-  load_nt<T, NV>(rb, B, K, n0, N, 0, K, tid);
+  StageNT<T, BM> sa;
+  StageNT<T, BN> sb;
+  sa.load(A, K, m0, M, 0, K, tid);
+  sb.load(B, K, n0, N, 0, K, tid);
   for (int k0 = 0; k0 < K; k0 += BK) {
-    store_nt<T, NV>(ra, As, tid);
-    store_nt<T, NV>(rb, Bs, tid);
+    sa.store(As, tid);
+    sb.store(Bs, tid);
     __syncthreads();
     if (k0 + BK < K) {
-      load_nt<T, NV>(ra, A, K, m0, M, k0 + BK, K, tid);
-      load_nt<T, NV>(rb, B, K, n0, N, k0 + BK, K, tid);
+      sa.load(A, K, m0, M, k0 + BK, K, tid);
+      sb.load(B, K, n0, N, k0 + BK, K, tid);
     }
     mma_tile<T>(acc, As, Bs, wm, wn, lane);
     __syncthreads();
   }
-  epilogue<T, EPI>(acc, m0, n0, wm, wn, lane, M, N, bias, aux, out);
+  if constexpr (sizeof(T) == 2 && EPI != EPI_F32) {
+    bf16_t *patch = reinterpret_cast<bf16_t *>(smem) + wave * 64 * (WN + 8);
+    epilogue_bf16<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, reinterpret_cast<const bf16_t *>(aux),
+                       static_cast<bf16_t *>(out));
+  } else {
+    epilogue_direct<T, EPI>(acc, m0, n0, wm, wn, lane, M, N, bias, aux, out);
+  }
 }
 
 template <typename T>
@@ -243,57 +718,45 @@ k_gemm_tn(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
           float *__restrict__ partial, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   constexpr int BK = Tile<T>::BK, LDK = Tile<T>::LDK;
-  __shared__ __attribute__((aligned(16))) T As[BM * LDK];
-  __shared__ __attribute__((aligned(16))) T Bs[BN * LDK];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *As = reinterpret_cast<T *>(smem);
+  T *Bs = As + BM * LDK;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int n_tiles = (N + BN - 1) / BN;
-  const int m0 = (blockIdx.x / n_tiles) * BM, n0 = (blockIdx.x % n_tiles) * BN;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / n_tiles) * BM, n0 = (tile % n_tiles) * BN;
   const int k_begin = blockIdx.z * k_chunk;
   const int k_end = min(K, k_begin + k_chunk);
 
-  f32x16_v acc[2][2];
+  f32x16_v acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  if constexpr (sizeof(T) == 2) {
-    // threads 0..127 stage A blocks, 128..255 stage B blocks
-    const bool isB = tid >= 128;
-    const int blk = tid & 127;
-    const T *src = isB ? B : A;
-    const int ld = isB ? N : M, row0 = isB ? n0 : m0, rows = isB ? N : M;
-    T *dst = isB ? Bs : As;
-    Pack16 r[8];
-    load_tn_bf16(r, src, ld, row0, rows, k_begin, k_end, blk);
-    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-      store_tn_bf16(r, dst, blk);
-      __syncthreads();
-      if (k0 + BK < k_end) load_tn_bf16(r, src, ld, row0, rows, k0 + BK, k_end, blk);
-      mma_tile<T>(acc, As, Bs, wm, wn, lane);
-      __syncthreads();
+  using SA = typename std::conditional<sizeof(T) == 2, StageTNbf16<BM>, StageTNf32<BM>>::type;
+  using SB = typename std::conditional<sizeof(T) == 2, StageTNbf16<BN>, StageTNf32<BN>>::type;
+  SA sa;
+  SB sb;
+  sa.load(A, M, m0, M, k_begin, k_end, tid);
+  sb.load(B, N, n0, N, k_begin, k_end, tid);
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+    sa.store(As, tid);
+    sb.store(Bs, tid);
+    __syncthreads();
+    if (k0 + BK < k_end) {
+      sa.load(A, M, m0, M, k0 + BK, k_end, tid);
+      sb.load(B, N, n0, N, k0 + BK, k_end, tid);
     }
-  } else {
-    Pack16 ra[2], rb[2];
-    load_tn_f32(ra, A, M, m0, M, k_begin, k_end, tid);
-    load_tn_f32(rb, B, N, n0, N, k_begin, k_end, tid);
-    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-      store_tn_f32(ra, As, tid);
-      store_tn_f32(rb, Bs, tid);
-      __syncthreads();
-      if (k0 + BK < k_end) {
-        load_tn_f32(ra, A, M, m0, M, k0 + BK, k_end, tid);
-        load_tn_f32(rb, B, N, n0, N, k0 + BK, k_end, tid);
-      }
-      mma_tile<T>(acc, As, Bs, wm, wn, lane);
-      __syncthreads();
-    }
+    mma_tile<T>(acc, As, Bs, wm, wn, lane);
+    __syncthreads();
   }
-  epilogue<T, EPI_F32>(acc, m0, n0, wm, wn, lane, M, N, nullptr, nullptr, partial + (size_t)blockIdx.z * M * N);
+  epilogue_direct<T, EPI_F32>(acc, m0, n0, wm, wn, lane, M, N, nullptr, nullptr,
+                              partial + (size_t)blockIdx.z * M * N);
 }
 
 // W -= lr * sum_z partial[z], z ascending
@@ -312,8 +775,25 @@ template <typename T>
 hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, const float *bias, const void *aux,
                   void *out, const int32_t *status, hipStream_t s) {
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
+  if constexpr (sizeof(T) == 2) {
+    if (K % DK == 0) {
+      const dim3 grid(((M + DM - 1) / DM) * ((N + DN - 1) / DN));
+#define GEAR_DMA(E)                                                                                               \
+  hipLaunchKernelGGL((k_gemm_nt_dma<E>), grid, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, \
+                     bias, (const bf16_t *)aux, out, status)
+      if (epi == EPI_BIAS_RELU)
+        GEAR_DMA(EPI_BIAS_RELU);
+      else if (epi == EPI_MASK)
+        GEAR_DMA(EPI_MASK);
+      else
+        GEAR_DMA(EPI_F32);
+#undef GEAR_DMA
+      return hipGetLastError();
+    }
+  }
+  const size_t smem = lds_bytes(sizeof(T), Tile<T>::LDK);
 #define GEAR_NT(E)                                                                                                  \
-  hipLaunchKernelGGL((k_gemm_nt<T, E>), grid, dim3(THREADS), 0, s, (const T *)A, (const T *)B, M, N, K, bias,       \
+  hipLaunchKernelGGL((k_gemm_nt<T, E>), grid, dim3(THREADS), smem, s, (const T *)A, (const T *)B, M, N, K, bias,    \
                      (const T *)aux, out, status)
   if (epi == EPI_BIAS_RELU)
     GEAR_NT(EPI_BIAS_RELU);
@@ -326,6 +806,16 @@ hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, co
 }
 
 }  // namespace
+
+int gemm_splitk_for(int M, int N, int K) {
+  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  int s = (512 + tiles - 1) / tiles;
+  int cap = K / 512;
+  if (cap < 1) cap = 1;
+  if (s > cap) s = cap;
+  if (s > 64) s = 64;
+  return s < 1 ? 1 : s;
+}
 
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue_kind,
                           const float *bias, const void *aux, void *out, const int32_t *status, hipStream_t s) {
@@ -341,13 +831,20 @@ hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M,
   int k_chunk = (K + splits - 1) / splits;
   k_chunk = ((k_chunk + bk - 1) / bk) * bk;
   if (k_chunk == 0) k_chunk = bk;
+  if (dtype == GEAR_BF16 && K % DK == 0 && M >= 8 && N >= 8) {
+    const int kc = ((((K + splits - 1) / splits) + DK - 1) / DK) * DK;
+    const dim3 grid_dma(((M + DM - 1) / DM) * ((N + DN - 1) / DN), 1, splits);
+    hipLaunchKernelGGL(k_gemm_tn_dma, grid_dma, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, kc,
+                       partial, status);
+    return hipGetLastError();
+  }
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN), 1, splits);
   if (dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_gemm_tn<bf16_t>, grid, dim3(THREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K,
-                       k_chunk, partial, status);
+    hipLaunchKernelGGL(k_gemm_tn<bf16_t>, grid, dim3(THREADS), lds_bytes(2, Tile<bf16_t>::LDK), s, (const bf16_t *)A,
+                       (const bf16_t *)B, M, N, K, k_chunk, partial, status);
   else
-    hipLaunchKernelGGL(k_gemm_tn<float>, grid, dim3(THREADS), 0, s, (const float *)A, (const float *)B, M, N, K,
-                       k_chunk, partial, status);
+    hipLaunchKernelGGL(k_gemm_tn<float>, grid, dim3(THREADS), lds_bytes(4, Tile<float>::LDK), s, (const float *)A,
+                       (const float *)B, M, N, K, k_chunk, partial, status);
   return hipGetLastError();
 }
 

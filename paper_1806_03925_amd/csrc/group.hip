@@ -74,36 +74,36 @@ __global__ void __launch_bounds__(kSortBlock) k_radix_hist(GroupBatch gb, int pa
   for (int d = threadIdx.x; d < radix; d += kSortBlock) p.block_hist[(size_t)blockIdx.x * radix + d] = hist[d];
 }
 
-// ---- radix pass: exclusive offsets.  block_hist[t][d] becomes the number of keys with digit d in
-// tiles before t; row n_tiles receives the number of keys with a smaller digit. -----------------------
-__global__ void __launch_bounds__(kMaxRadix) k_radix_scan(GroupBatch gb, int pass, const int32_t *status) {
+// ---- radix pass: offsets over tiles.  block_hist[t][d] becomes the number of keys with digit d in
+// tiles before t; row n_tiles receives the total of digit d.  One workgroup per 64 digits; its four
+// waves split the tiles into four contiguous ranges (integer sums: any shape gives the same result).
+__global__ void __launch_bounds__(256) k_radix_scan(GroupBatch gb, int pass, const int32_t *status) {
   if (*status != 0) return;
-  const GroupProblem &p = gb.p[blockIdx.x];
-  if (pass >= p.passes || p.n <= 0) return;
-  __shared__ int totals[kMaxRadix];
-  __shared__ int wave_tot[kMaxRadix / kWave];
+  const GroupProblem &p = gb.p[blockIdx.y];
   const int radix = 1 << p.digit_bits;
+  if (pass >= p.passes || p.n <= 0 || (int)blockIdx.x * 64 >= radix) return;
+  __shared__ int range_sum[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = blockIdx.x * 64 + lane;
   const int n_tiles = (p.n + kSortTile - 1) / kSortTile;
-  const int d = threadIdx.x;
+  const int per = (n_tiles + 3) / 4;
+  const int t0 = min(n_tiles, wave * per), t1 = min(n_tiles, t0 + per);
+  int32_t *col = p.block_hist + d;
+  int sum = 0;
+  if (d < radix)
+    for (int t = t0; t < t1; ++t) sum += col[(size_t)t * radix];
+  range_sum[wave][lane] = sum;
+  __syncthreads();
   int run = 0;
+  for (int w = 0; w < wave; ++w) run += range_sum[w][lane];
   if (d < radix) {
-    for (int t = 0; t < n_tiles; ++t) {
-      int32_t *cell = p.block_hist + (size_t)t * radix + d;
-      const int c = *cell;
-      *cell = run;
+    for (int t = t0; t < t1; ++t) {
+      const int c = col[(size_t)t * radix];
+      col[(size_t)t * radix] = run;
       run += c;
     }
+    if (wave == 3) col[(size_t)n_tiles * radix] = run;  // the last range ends with the digit's total
   }
-  // exclusive scan of `run` over digits (blockDim = 512 = 8 waves)
-  const int lane = d & 63, wave = d >> 6;
-  const int inc = wave_inclusive_scan(d < radix ? run : 0, lane);
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave; ++w) base += wave_tot[w];
-  totals[d] = base + inc - (d < radix ? run : 0);
-  __syncthreads();
-  if (d < radix) p.block_hist[(size_t)n_tiles * radix + d] = totals[d];
 }
 
 // ---- radix pass: stable scatter ---------------------------------------------------------------------
@@ -116,13 +116,22 @@ __global__ void __launch_bounds__(kSortBlock) k_radix_scatter(GroupBatch gb, int
   // cnt[round][wave][digit]: keys with that digit seen by that wave in that round
   __shared__ uint16_t cnt[kSortItems * 4 * kMaxRadix];
   __shared__ int digit_off[kMaxRadix];
+  __shared__ int scan_smem[8];
   const int radix = 1 << p.digit_bits, shift = pass * p.digit_bits;
   const int n_tiles = (p.n + kSortTile - 1) / kSortTile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   for (int i = threadIdx.x; i < kSortItems * 4 * radix / 2; i += kSortBlock) reinterpret_cast<uint32_t *>(cnt)[i] = 0u;
-  for (int d = threadIdx.x; d < radix; d += kSortBlock)
-    digit_off[d] = p.block_hist[(size_t)blockIdx.x * radix + d] + p.block_hist[(size_t)n_tiles * radix + d];
+  {
+    // exclusive scan of the digit totals (radix <= 2 * kSortBlock: two adjacent digits per thread)
+    const int d0 = 2 * threadIdx.x, d1 = d0 + 1;
+    const int c0 = d0 < radix ? p.block_hist[(size_t)n_tiles * radix + d0] : 0;
+    const int c1 = d1 < radix ? p.block_hist[(size_t)n_tiles * radix + d1] : 0;
+    int total;
+    const int before = block_exclusive_scan(c0 + c1, &total, scan_smem);
+    if (d0 < radix) digit_off[d0] = before + p.block_hist[(size_t)blockIdx.x * radix + d0];
+    if (d1 < radix) digit_off[d1] = before + c0 + p.block_hist[(size_t)blockIdx.x * radix + d1];
+  }
   __syncthreads();
 
   const int32_t *keys_in = pass_keys(p, pass);
@@ -340,7 +349,7 @@ hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t
   const dim3 grid(max_tiles, gb.count);
   for (int pass = 0; pass < max_passes; ++pass) {
     hipLaunchKernelGGL(k_radix_hist, grid, dim3(kSortBlock), 0, s, gb, pass, status);
-    hipLaunchKernelGGL(k_radix_scan, dim3(gb.count), dim3(kMaxRadix), 0, s, gb, pass, status);
+    hipLaunchKernelGGL(k_radix_scan, dim3(kMaxRadix / 64, gb.count), dim3(256), 0, s, gb, pass, status);
     hipLaunchKernelGGL(k_radix_scatter, grid, dim3(kSortBlock), 0, s, gb, pass, status);
   }
   hipLaunchKernelGGL(k_seg_count, grid, dim3(kSortBlock), 0, s, gb, status);

@@ -38,39 +38,98 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One wavefront per view: logit z = h . w + b, loss term, dLoss/dz = (sigmoid(z) - y) / B, and the
-// delta of the last hidden layer, delta[b, j] = dz * w[j] * [h[b, j] > 0].  Each workgroup keeps a
-// running loss sum over its views in a fixed order and leaves it in loss_partial[blockIdx].
+constexpr int kMaxVecPerLane = 4;  // a lane owns up to 4 16-byte pieces of a row: H <= 2048 (bf16) / 1024 (fp32)
+
+// Logit layer, loss and everything that hangs on dLoss/dz.  One wavefront per view, a workgroup
+// owns a contiguous range of views and its waves take them round-robin, so every sum below has a
+// shape fixed by B alone:
+//   z = h . w + b,  loss term,  dz = (sigmoid(z) - y) / B,
+//   delta[b, j] = dz * w[j] * [h[b, j] > 0]                      (delta of the last hidden layer)
+//   part_w[block][j] = sum_b dz_b h[b, j],  part_b[block] = sum_b dz_b,  part_loss[block] = sum_b loss_b
 template <typename T>
 __global__ void __launch_bounds__(256)
 k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__restrict__ bias,
-             const float *__restrict__ label, int B, int H, float *__restrict__ logits, float *__restrict__ dz_out,
-             T *__restrict__ delta, float *__restrict__ loss_partial, const int32_t *__restrict__ status) {
+             const float *__restrict__ label, int B, int H, int rows_per_block, float *__restrict__ logits,
+             float *__restrict__ dz_out, T *__restrict__ delta, float *__restrict__ part_w,
+             float *__restrict__ part_b, float *__restrict__ part_loss, const int32_t *__restrict__ status) {
   if (*status != 0) return;
-  __shared__ float wave_loss[4];
+  constexpr int VEC = Vec16<T>::N;
+  __shared__ float s_red[4][2];
+  extern __shared__ float s_w[];  // [4][H] per-wave weight-gradient sums
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_vec = H / VEC;
   const float b0 = bias[0], invB = 1.0f / (float)B;
-  float loss_acc = 0.0f;
-  for (int view = blockIdx.x * 4 + wave; view < B; view += gridDim.x * 4) {
+
+  Vec16<T> wv[kMaxVecPerLane];
+  float gw[kMaxVecPerLane][VEC];
+#pragma unroll
+  for (int i = 0; i < kMaxVecPerLane; ++i) {
+    const int v = lane + i * kWave;
+    if (v < n_vec) wv[i].v = *reinterpret_cast<const decltype(wv[i].v) *>(w + v * VEC);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) gw[i][e] = 0.0f;
+  }
+  float loss_acc = 0.0f, dz_acc = 0.0f;
+  const int r0 = blockIdx.x * rows_per_block, r1 = min(B, r0 + rows_per_block);
+  for (int view = r0 + wave; view < r1; view += 4) {
     const T *hr = h + (size_t)view * H;
+    Vec16<T> hv[kMaxVecPerLane];
     float dot = 0.0f;
-    for (int j = lane; j < H; j += kWave) dot += to_f32<T>(hr[j]) * to_f32<T>(w[j]);
+#pragma unroll
+    for (int i = 0; i < kMaxVecPerLane; ++i) {
+      const int v = lane + i * kWave;
+      if (v < n_vec) {
+        hv[i].v = *reinterpret_cast<const decltype(hv[i].v) *>(hr + v * VEC);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dot += hv[i].get(e) * wv[i].get(e);
+      }
+    }
     const float z = wave_sum(dot) + b0;
     const float y = label[view];
-    const float e = expf(-fabsf(z));
-    const float sig = z >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+    const float ex = expf(-fabsf(z));
+    const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
     const float dz = (sig - y) * invB;
-    loss_acc += fmaxf(z, 0.0f) - z * y + log1pf(e);
+    loss_acc += fmaxf(z, 0.0f) - z * y + log1pf(ex);
+    dz_acc += dz;
     if (lane == 0) {
       logits[view] = z;
       dz_out[view] = dz;
     }
     T *dr = delta + (size_t)view * H;
-    for (int j = lane; j < H; j += kWave) dr[j] = from_f32<T>(to_f32<T>(hr[j]) > 0.0f ? dz * to_f32<T>(w[j]) : 0.0f);
+#pragma unroll
+    for (int i = 0; i < kMaxVecPerLane; ++i) {
+      const int v = lane + i * kWave;
+      if (v < n_vec) {
+        Vec16<T> dv = hv[i];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float hval = hv[i].get(e);
+          gw[i][e] += dz * hval;
+          dv.set(e, hval > 0.0f ? dz * wv[i].get(e) : 0.0f);
+        }
+        *reinterpret_cast<decltype(dv.v) *>(dr + v * VEC) = dv.v;
+      }
+    }
   }
-  if (lane == 0) wave_loss[wave] = loss_acc;
+  // combine the four waves in wave order
+#pragma unroll
+  for (int i = 0; i < kMaxVecPerLane; ++i) {
+    const int v = lane + i * kWave;
+    if (v < n_vec)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) s_w[wave * H + v * VEC + e] = gw[i][e];
+  }
+  if (lane == 0) {
+    s_red[wave][0] = loss_acc;
+    s_red[wave][1] = dz_acc;
+  }
   __syncthreads();
-  if (threadIdx.x == 0) loss_partial[blockIdx.x] = ((wave_loss[0] + wave_loss[1]) + wave_loss[2]) + wave_loss[3];
+  for (int j = threadIdx.x; j < H; j += blockDim.x)
+    part_w[(size_t)blockIdx.x * H + j] = ((s_w[j] + s_w[H + j]) + s_w[2 * H + j]) + s_w[3 * H + j];
+  if (threadIdx.x == 0) {
+    part_loss[blockIdx.x] = ((s_red[0][0] + s_red[1][0]) + s_red[2][0]) + s_red[3][0];
+    part_b[blockIdx.x] = ((s_red[0][1] + s_red[1][1]) + s_red[2][1]) + s_red[3][1];
+  }
 }
 
 __global__ void __launch_bounds__(64) k_loss_final(const float *__restrict__ loss_partial, int n, int B,
@@ -82,34 +141,71 @@ __global__ void __launch_bounds__(64) k_loss_final(const float *__restrict__ los
   if (threadIdx.x == 0) *loss = v / (float)B;
 }
 
-// partial[chunk][j] = sum over the chunk's rows (ascending) of weight[row] * src[row][j]
+// partial[chunk][j] = sum over the chunk's rows of src[row][j].  A thread owns one 16-byte piece of
+// the row and every RS-th row of the chunk; the RS row-lanes are then added in order.
 template <typename T>
 __global__ void __launch_bounds__(256)
-k_colsum_partial(const T *__restrict__ src, const float *__restrict__ row_weight, int B, int H,
-                 float *__restrict__ partial, const int32_t *__restrict__ status) {
+k_colsum_partial(const T *__restrict__ src, int B, int H, int rows_per_chunk, float *__restrict__ partial,
+                 const int32_t *__restrict__ status) {
   if (*status != 0) return;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= H) return;
-  const int r0 = blockIdx.y * kColsumRows, r1 = min(B, r0 + kColsumRows);
-  float acc = 0.0f;
-  if (row_weight) {
-    for (int r = r0; r < r1; ++r) acc += row_weight[r] * to_f32<T>(src[(size_t)r * H + j]);
-  } else {
-    for (int r = r0; r < r1; ++r) acc += to_f32<T>(src[(size_t)r * H + j]);
+  constexpr int VEC = Vec16<T>::N;
+  extern __shared__ float s_part[];  // [RS][cols of this block]
+  const int n_vec = H / VEC;
+  const int vec_here = min(n_vec - (int)blockIdx.x * 256, 256);  // column pieces handled by this block
+  const int RS = 256 / vec_here;                                  // row lanes
+  const int cv = threadIdx.x % vec_here, rl = threadIdx.x / vec_here;
+  const int col = (blockIdx.x * 256 + cv) * VEC;
+  const int r0 = blockIdx.y * rows_per_chunk, r1 = min(B, r0 + rows_per_chunk);
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+  if (rl < RS) {
+    for (int r = r0 + rl; r < r1; r += RS) {
+      Vec16<T> v;
+      v.v = *reinterpret_cast<const decltype(v.v) *>(src + (size_t)r * H + col);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += v.get(e);
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s_part[(rl * vec_here + cv) * VEC + e] = acc[e];
   }
-  partial[(size_t)blockIdx.y * H + j] = acc;
+  __syncthreads();
+  for (int j = threadIdx.x; j < vec_here * VEC; j += blockDim.x) {
+    float t = 0.0f;
+    for (int k = 0; k < RS; ++k) t += s_part[k * vec_here * VEC + j];
+    partial[(size_t)blockIdx.y * H + blockIdx.x * 256 * VEC + j] = t;
+  }
 }
 
-// dst[j] -= lr * sum_chunk partial[chunk][j], chunks ascending
-__global__ void __launch_bounds__(256) k_colsum_sgd(const float *__restrict__ partial, int chunks, int H,
-                                                    float *__restrict__ dst, float lr,
-                                                    const int32_t *__restrict__ status) {
+// dst[j] -= lr * sum_p partial[p][j].  Eight columns per workgroup and 32 row lanes, each adding
+// every 32nd partial in order (eight loads in flight); then the 32 lanes are added in order.
+__global__ void __launch_bounds__(256) k_partial_sgd(const float *__restrict__ partial, int P, int H,
+                                                     float *__restrict__ dst, float lr,
+                                                     const int32_t *__restrict__ status) {
   if (*status != 0) return;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= H) return;
-  float g = 0.0f;
-  for (int c = 0; c < chunks; ++c) g += partial[(size_t)c * H + j];
-  dst[j] -= lr * g;
+  __shared__ float s[32][8];
+  const int c = threadIdx.x & 7, g = threadIdx.x >> 3;
+  const int j = blockIdx.x * 8 + c;
+  float acc = 0.0f;
+  if (j < H) {
+    int p = g;
+    for (; p + 32 * 7 < P; p += 32 * 8) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = partial[(size_t)(p + 32 * i) * H + j];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc += v[i];
+    }
+    for (; p < P; p += 32) acc += partial[(size_t)p * H + j];
+  }
+  s[g][c] = acc;
+  __syncthreads();
+  if (g == 0 && j < H) {
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) t += s[k][c];
+    dst[j] -= lr * t;
+  }
 }
 
 }  // namespace
@@ -124,39 +220,52 @@ hipError_t launch_cast_weights(const float *w, int rows, int cols, int dtype, vo
   return hipGetLastError();
 }
 
-hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, const float *bias_last,
+int logit_blocks(int B) {
+  int blocks = (B + 31) / 32;
+  return blocks < 1 ? 1 : (blocks > kLossBlocks ? kLossBlocks : blocks);
+}
+
+// Forward logit + loss + delta of the last hidden layer, then SGD on the logit layer's weight and bias.
+hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
                              const float *label, int B, int H, float *logits, float *dz, void *delta,
-                             float *loss_partial, float *loss, const int32_t *status, hipStream_t s) {
+                             float *partials, float *loss, float lr, const int32_t *status, hipStream_t s) {
   if (B <= 0) return hipSuccess;
+  const int blocks = logit_blocks(B);
+  const int rows_per_block = (B + blocks - 1) / blocks;
+  float *part_w = partials, *part_b = partials + (size_t)kLossBlocks * H, *part_loss = part_b + kLossBlocks;
+  const size_t smem = 4 * (size_t)H * sizeof(float);
   if (dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_logit_loss<bf16_t>, dim3(kLossBlocks), dim3(256), 0, s, (const bf16_t *)h,
-                       (const bf16_t *)wc_last, bias_last, label, B, H, logits, dz, (bf16_t *)delta, loss_partial,
-                       status);
+    hipLaunchKernelGGL(k_logit_loss<bf16_t>, dim3(blocks), dim3(256), smem, s, (const bf16_t *)h,
+                       (const bf16_t *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz, (bf16_t *)delta,
+                       part_w, part_b, part_loss, status);
   else
-    hipLaunchKernelGGL(k_logit_loss<float>, dim3(kLossBlocks), dim3(256), 0, s, (const float *)h,
-                       (const float *)wc_last, bias_last, label, B, H, logits, dz, (float *)delta, loss_partial,
-                       status);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, s, loss_partial, kLossBlocks, B, loss, status);
+    hipLaunchKernelGGL(k_logit_loss<float>, dim3(blocks), dim3(256), smem, s, (const float *)h,
+                       (const float *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz, (float *)delta,
+                       part_w, part_b, part_loss, status);
+  hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, s, part_loss, blocks, B, loss, status);
+  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, part_w, blocks, H, w_last, lr, status);
+  hipLaunchKernelGGL(k_partial_sgd, dim3(1), dim3(256), 0, s, part_b, blocks, 1, bias_last, lr, status);
   return hipGetLastError();
 }
 
-hipError_t launch_colsum_sgd(int dtype, const void *src, const float *row_weight, int B, int H, float *partial,
-                             float *dst, float lr, const int32_t *status, hipStream_t s) {
+size_t logit_partial_floats(int H) { return (size_t)kLossBlocks * H + 2 * (size_t)kLossBlocks; }
+
+// dst[j] -= lr * sum_b src[b][j]   (bias gradient of a hidden layer)
+hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, float lr,
+                             const int32_t *status, hipStream_t s) {
   if (B <= 0 || H <= 0) return hipSuccess;
   const int chunks = (B + kColsumRows - 1) / kColsumRows;
-  const int bs = H >= 256 ? 256 : 64;
-  const dim3 grid((H + bs - 1) / bs, chunks);
+  const int vec = dtype == GEAR_BF16 ? 8 : 4;
+  const int n_vec = H / vec;
+  const dim3 grid((n_vec + 255) / 256, chunks);
+  const size_t smem = 256 * (size_t)vec * sizeof(float);
   if (dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_colsum_partial<bf16_t>, grid, dim3(bs), 0, s, (const bf16_t *)src, row_weight, B, H, partial,
-                       status);
+    hipLaunchKernelGGL(k_colsum_partial<bf16_t>, grid, dim3(256), smem, s, (const bf16_t *)src, B, H, kColsumRows,
+                       partial, status);
   else
-    hipLaunchKernelGGL(k_colsum_partial<float>, grid, dim3(bs), 0, s, (const float *)src, row_weight, B, H, partial,
-                       status);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_colsum_sgd, dim3((H + 255) / 256), dim3(256), 0, s, partial, chunks, H, dst, lr, status);
+    hipLaunchKernelGGL(k_colsum_partial<float>, grid, dim3(256), smem, s, (const float *)src, B, H, kColsumRows,
+                       partial, status);
+  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, partial, chunks, H, dst, lr, status);
   return hipGetLastError();
 }
 

@@ -1,64 +1,182 @@
 // SGD on the touched embedding rows (Section 3, step 4: the Fastgear Worker applies the Sparse
 // Part's gradients every step).
 //
-// The gradient of a row is the sum of dLoss/dx over the views that used it.  The views of one id
-// are a segment of the stable grouping, ascending in batch position, and are summed in that order
-// by one wavefront, which then writes the row once: no atomics, so the result does not depend on
-// scheduling.
+// The gradient of a row is the sum of dLoss/dx over the views that used it.  After the stable
+// sort by id those views are a run of the sorted positions, ascending in batch position.  Zipf
+// traffic makes a few runs thousands of views long, so the sum has a fixed two-level shape that
+// depends on the data only, never on scheduling: the sorted positions are cut into chunks of kChunk
+// and a worker adds the rows of its chunk run by run, in order.  A run that lies inside one
+// chunk is finished on the spot (one read-modify-write of the row).  A run that crosses chunk
+// borders leaves one partial per chunk; the worker of the chunk where the run starts then adds
+// those partials in chunk order and writes the row.  No atomics anywhere.
+//
+// A worker is d/4 lanes, each owning one float4 column group of the row.
 #include "gear_internal.hpp"
 
 namespace gear {
 namespace {
 
+constexpr int kChunk = 16;
+
+struct Table {
+  const int32_t *keys;   // sorted ids
+  const int32_t *perm;   // batch position of each sorted position
+  int n;
+  void *rows;            // embedding table
+  int col0;              // first column of this table's slice inside a dx row
+  float *part_first;     // [chunks x d] partial of a run that began in an earlier chunk
+  float *part_last;      // [chunks x d] partial of a run that begins here and goes on
+};
+
+template <typename ET> __device__ __forceinline__ void apply_row(ET *row, int c4, float4 g, float lr);
+template <> __device__ __forceinline__ void apply_row<float>(float *row, int c4, float4 g, float lr) {
+  float4 *cell = reinterpret_cast<float4 *>(row) + c4;
+  float4 v = *cell;
+  v.x -= lr * g.x;
+  v.y -= lr * g.y;
+  v.z -= lr * g.z;
+  v.w -= lr * g.w;
+  *cell = v;
+}
+template <> __device__ __forceinline__ void apply_row<bf16_t>(bf16_t *row, int c4, float4 g, float lr) {
+  uint2 *cell = reinterpret_cast<uint2 *>(row) + c4;
+  uint2 v = *cell;
+  const float a = __uint_as_float(v.x << 16) - lr * g.x, b = __uint_as_float(v.x & 0xffff0000u) - lr * g.y;
+  const float c = __uint_as_float(v.y << 16) - lr * g.z, d = __uint_as_float(v.y & 0xffff0000u) - lr * g.w;
+  v.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  v.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+  *cell = v;
+}
+
+__device__ __forceinline__ void add4(float4 &a, const float4 &b) {
+  a.x += b.x;
+  a.y += b.y;
+  a.z += b.z;
+  a.w += b.w;
+}
+
+// level 1: one worker per chunk of sorted positions
 template <typename ET>
 __global__ void __launch_bounds__(256)
-k_embedding_update(GroupProblem users, GroupProblem urls, const float *__restrict__ dx, int F, int d,
-                   ET *__restrict__ user_emb, ET *__restrict__ url_emb, float lr, const int32_t *__restrict__ status) {
+k_embedding_chunks(Table users, Table urls, const float *__restrict__ dx, int F, int d, int lanes_per_worker, float lr,
+                   const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  const Table &t = blockIdx.y == 1 ? urls : users;
+  const int tid = blockIdx.x * blockDim.x + threadIdx.x;
+  const int chunk = tid / lanes_per_worker, c4 = tid % lanes_per_worker;
+  const int q_begin = chunk * kChunk;
+  if (q_begin >= t.n || c4 >= d / 4) return;
+  const int q_end = min(t.n, q_begin + kChunk);
+  const float *col = dx + t.col0 + 4 * c4;
+
+  // ids, batch positions and rows of the whole chunk first, so that all loads are in flight at once
+  int keys[kChunk + 1], pos[kChunk];
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i) {
+    const int q = q_begin + i;
+    keys[i] = q < t.n ? t.keys[q] : -1;
+    pos[i] = q < t.n ? t.perm[q] : 0;
+  }
+  keys[kChunk] = q_begin + kChunk < t.n ? t.keys[q_begin + kChunk] : -1;
+  float4 row[kChunk];
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i)
+    row[i] = q_begin + i < q_end ? *reinterpret_cast<const float4 *>(col + (size_t)pos[i] * F)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+
+  bool starts_here = q_begin == 0 || t.keys[q_begin - 1] != keys[0];
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i) {
+    if (q_begin + i < q_end) {
+      add4(sum, row[i]);
+      const bool last_in_chunk = q_begin + i + 1 == q_end;
+      const bool ends_here = keys[i + 1] != keys[i];
+      if (ends_here || last_in_chunk) {
+        if (starts_here && ends_here) {
+          apply_row<ET>(static_cast<ET *>(t.rows) + (size_t)keys[i] * d, c4, sum, lr);
+        } else {
+          float *dst = (starts_here ? t.part_last : t.part_first) + (size_t)chunk * d;
+          *reinterpret_cast<float4 *>(dst + 4 * c4) = sum;
+        }
+        sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        starts_here = true;  // a run that begins after the first one starts inside this chunk
+      }
+    }
+  }
+}
+
+// level 2: one wavefront per chunk; if a border-crossing run starts in this chunk the wave adds
+// the run's partials in chunk order (lane = column) and writes the row
+template <typename ET>
+__global__ void __launch_bounds__(256)
+k_embedding_spans(Table users, Table urls, const int32_t *__restrict__ user_pos_seg,
+                  const int32_t *__restrict__ user_segoff, const int32_t *__restrict__ url_pos_seg,
+                  const int32_t *__restrict__ url_segoff, int d, float lr, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   const bool second = blockIdx.y == 1;
-  const GroupProblem &g = second ? urls : users;
-  ET *table = second ? url_emb : user_emb;
-  const int col0 = second ? d : 0;
+  const Table &t = second ? urls : users;
+  const int32_t *pos_seg = second ? url_pos_seg : user_pos_seg;
+  const int32_t *segoff = second ? url_segoff : user_segoff;
   const int lane = threadIdx.x & 63;
-  const int n_seg = *g.n_unique;
-  const int waves = gridDim.x * (blockDim.x / kWave);
-  for (int seg = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave; seg < n_seg; seg += waves) {
-    const int64_t id = g.unique[seg];
-    const int q0 = g.segoff[seg], q1 = g.segoff[seg + 1];
-    for (int c = lane; c < d; c += kWave) {
-      float sum = 0.0f;
-      int q = q0;
-      for (; q + 4 <= q1; q += 4) {  // four rows in flight, added in order
-        const float v0 = dx[(size_t)g.perm[q] * F + col0 + c];
-        const float v1 = dx[(size_t)g.perm[q + 1] * F + col0 + c];
-        const float v2 = dx[(size_t)g.perm[q + 2] * F + col0 + c];
-        const float v3 = dx[(size_t)g.perm[q + 3] * F + col0 + c];
-        sum = (((sum + v0) + v1) + v2) + v3;
-      }
-      for (; q < q1; ++q) sum += dx[(size_t)g.perm[q] * F + col0 + c];
-      ET *cell = table + id * d + c;
-      *cell = from_f32<ET>(to_f32<ET>(*cell) - lr * sum);
+  const int chunk = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int q_begin = chunk * kChunk;
+  if (q_begin >= t.n) return;
+  const int q_last = min(t.n, q_begin + kChunk) - 1;
+  if (q_last + 1 >= t.n) return;              // nothing after this chunk
+  const int key = t.keys[q_last];
+  if (t.keys[q_last + 1] != key) return;      // the last run ends inside this chunk
+  const int seg = pos_seg[q_last];
+  const int s0 = segoff[seg], s1 = segoff[seg + 1];
+  if (s0 < q_begin) return;                   // the run began in an earlier chunk: not ours
+  const int k_last = (s1 - 1) / kChunk;
+  for (int c = lane; c < d; c += kWave) {
+    float sum = t.part_last[(size_t)chunk * d + c];
+    int k = chunk + 1;
+    for (; k + 8 <= k_last + 1; k += 8) {     // eight partials in flight, added in order
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = t.part_first[(size_t)(k + i) * d + c];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += v[i];
     }
+    for (; k <= k_last; ++k) sum += t.part_first[(size_t)k * d + c];
+    ET *cell = static_cast<ET *>(t.rows) + (size_t)key * d + c;
+    *cell = from_f32<ET>(to_f32<ET>(*cell) - lr * sum);
   }
 }
 
 }  // namespace
 
 hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
-                                   const float *dx, int F, void *user_emb, void *url_emb, float lr,
+                                   const float *dx, int F, void *user_emb, void *url_emb, float *partials, float lr,
                                    const int32_t *status, hipStream_t s) {
   const int n = users.n > urls.n ? users.n : urls.n;
   if (n <= 0) return hipSuccess;
-  int blocks = (n + 3) / 4;
-  if (blocks > 4096) blocks = 4096;
-  const dim3 grid(blocks, 2);
-  if (cfg.emb_dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_embedding_update<bf16_t>, grid, dim3(256), 0, s, users, urls, dx, F, cfg.emb_dim,
-                       (bf16_t *)user_emb, (bf16_t *)url_emb, lr, status);
-  else
-    hipLaunchKernelGGL(k_embedding_update<float>, grid, dim3(256), 0, s, users, urls, dx, F, cfg.emb_dim,
-                       (float *)user_emb, (float *)url_emb, lr, status);
+  const int d = cfg.emb_dim;
+  int lanes = 1;
+  while (lanes < d / 4) lanes <<= 1;  // power of two so that workers do not straddle wavefronts
+  const int chunks = (n + kChunk - 1) / kChunk;
+  const size_t per = (size_t)((cfg.max_batch + kChunk - 1) / kChunk) * d;
+  Table tu = {users.sorted_keys, users.perm, users.n, user_emb, 0, partials, partials + per};
+  Table tl = {urls.sorted_keys, urls.perm, urls.n, url_emb, d, partials + 2 * per, partials + 3 * per};
+  const long long threads = (long long)chunks * lanes;
+  const dim3 grid((unsigned)((threads + 255) / 256), 2);
+  const dim3 grid2((chunks + 3) / 4, 2);
+  if (cfg.emb_dtype == GEAR_BF16) {
+    hipLaunchKernelGGL(k_embedding_chunks<bf16_t>, grid, dim3(256), 0, s, tu, tl, dx, F, d, lanes, lr, status);
+    hipLaunchKernelGGL(k_embedding_spans<bf16_t>, grid2, dim3(256), 0, s, tu, tl, users.pos_seg, users.segoff,
+                       urls.pos_seg, urls.segoff, d, lr, status);
+  } else {
+    hipLaunchKernelGGL(k_embedding_chunks<float>, grid, dim3(256), 0, s, tu, tl, dx, F, d, lanes, lr, status);
+    hipLaunchKernelGGL(k_embedding_spans<float>, grid2, dim3(256), 0, s, tu, tl, users.pos_seg, users.segoff,
+                       urls.pos_seg, urls.segoff, d, lr, status);
+  }
   return hipGetLastError();
+}
+
+size_t embedding_partial_floats(const gear_config &cfg) {
+  return 4 * (size_t)((cfg.max_batch + kChunk - 1) / kChunk) * cfg.emb_dim;
 }
 
 }  // namespace gear

@@ -352,3 +352,38 @@ def test_refresh_overwrites_rows_and_nothing_else():
     torch.cuda.synchronize()
     assert int(st.status.item()) == g.GEAR_ERR_RANGE
     assert torch.equal(st.dfv_cache[4:], full[4:]) and not st.dfv_cache[3].any()
+
+
+# ------------------------------------------------------------------ matrix products on their own
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K", [(300, 136, 200), (1, 8, 8), (517, 1152, 1024), (2048, 256, 64)])
+def test_gemm_forms_against_fp32_matmul(dtype, M, N, K):
+    """Both forms against a plain fp32/fp64 matmul of the same operands (ragged tiles included)."""
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cuda").manual_seed(M * 31 + N * 7 + K)
+    A = torch.randn((M, K), generator=gen, device="cuda").to(td)
+    Bm = torch.randn((N, K), generator=gen, device="cuda").to(td)
+    ref = A.double() @ Bm.double().T
+    scale = ref.abs().amax(dim=1, keepdim=True).clamp_min(1e-30)
+    out = g.gear_gemm(A, Bm, form=0, epilogue=2)
+    torch.cuda.synchronize()
+    assert ((out.double() - ref).abs() / scale).max().item() < 1e-5
+    # bias + ReLU, result rounded to the operand type
+    bias = torch.randn(N, generator=gen, device="cuda")
+    want = torch.relu(ref + bias.double())
+    got = g.gear_gemm(A, Bm, form=0, epilogue=0, bias=bias)
+    tol = 2.0 ** -8 if dtype == "bf16" else 1e-5
+    assert ((got.double() - want).abs() <= tol * want.abs() + 1e-5 * scale).all()
+    # ReLU mask from an activation tensor
+    aux = torch.randn((M, N), generator=gen, device="cuda").to(td)
+    want = torch.where(aux.double() > 0, ref, torch.zeros_like(ref))
+    got = g.gear_gemm(A, Bm, form=0, epilogue=1, aux=aux)
+    assert ((got.double() - want).abs() <= tol * want.abs() + 1e-5 * scale).all()
+    assert ((got == 0) == ((aux <= 0) | (want == 0))).all()
+    # wgrad form: contraction over the rows, several split counts give the same shape of result
+    At, Bt = A.T.contiguous(), Bm.T.contiguous()        # [K x M], [K x N]
+    if M % 8 == 0 and N % 8 == 0:
+        for splits in (1, 3):
+            out = g.gear_gemm(At, Bt, form=1, splits=splits)
+            torch.cuda.synchronize()
+            assert ((out.double() - ref).abs() / scale).max().item() < 1e-5
