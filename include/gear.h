@@ -11,10 +11,13 @@
  * arrived and are then averaged (Section 1, third point; Section 3, step 6).
  *
  * This library is that per-step work.  All pointers named "device" are device
- * memory owned by the caller; the library allocates nothing, keeps no state
- * between calls, enqueues its kernels on the given hipStream_t (passed as
- * void*) and returns without synchronising.  Results are valid once the caller
- * has synchronised that stream.
+ * memory owned by the caller; the library allocates no device memory and keeps
+ * no state between calls except one helper stream and two events per device,
+ * created at the first gear_step (default priority; part of a step runs on it,
+ * forked from and joined back into the caller's stream).  Calls enqueue their
+ * kernels on the given hipStream_t (passed as void*) and return without
+ * synchronising.  Results are valid once the caller has synchronised that
+ * stream.  Steps on one device must not overlap each other.
  *
  * Errors.  Everything the host can check (NULL pointers, dimensions, M < 1,
  * sizes over the configured maxima, a workspace that is too small) is reported

@@ -175,6 +175,30 @@ bool make_layout(const gear_config &c, Layout *lay) {
 
 using namespace gear;
 
+// One helper stream and two events per device, created on first use and kept for the life of the
+// process: the integer grouping of a step runs beside its gather and forward pass.
+namespace {
+struct SideLane {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool ready = false;
+};
+SideLane g_side[64];
+
+SideLane *side_lane() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  SideLane &l = g_side[dev];
+  if (!l.ready) {
+    if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&l.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    l.ready = true;
+  }
+  return &l;
+}
+}  // namespace
+
 #define GEAR_HIP(expr)                             \
   do {                                             \
     if ((expr) != hipSuccess) return GEAR_ERR_HIP; \
@@ -298,7 +322,6 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   gb.p[0] = make_problem(lay, ws, 0, b->user_id, B, cfg->n_users);
   gb.p[1] = make_problem(lay, ws, 1, b->url_id, B, cfg->n_urls);
   gb.p[2] = make_problem(lay, ws, 2, b->img_id, b->nnz, cfg->n_images);
-  GEAR_RUN("group_ids", launch_group(gb, status, s));
   AccumPlan plan;
   plan.tile_units = (int32_t *)(ws + lay.tile_units);
   plan.tile_emits = (int32_t *)(ws + lay.tile_emits);
@@ -306,7 +329,20 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   plan.unit_slot = (int32_t *)(ws + lay.unit_slot);
   plan.unit_seg = (int32_t *)(ws + lay.unit_seg);
   plan.n_units = (int32_t *)(ws + lay.n_units);
-  GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, counts, M, out->ready_cap, out->n_ready, status, s));
+  // The grouping depends on the ids only: it runs on the helper stream while the main stream gathers
+  // and runs the forward pass, and is joined before the first kernel that changes caller state.
+  SideLane *side = side_lane();
+  if (!side) return GEAR_ERR_HIP;
+  GEAR_HIP(hipEventRecord(side->fork, s));
+  GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+  {
+    hipStream_t main_stream = s;
+    hipStream_t s = side->stream;  // the two launches below go to the helper stream
+    (void)main_stream;
+    GEAR_RUN("group_ids", launch_group(gb, status, s));
+    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, counts, M, out->ready_cap, out->n_ready, status, s));
+  }
+  GEAR_HIP(hipEventRecord(side->join, side->stream));
 
   // forward
   void *x = ws + lay.x;
@@ -322,6 +358,7 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
                                      ws + lay.h[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
+  GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
   GEAR_RUN("logit_loss_sgd",
            launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.w_off[L - 1],
                              t->mlp_params + lay.b_off[L - 1], b->label, B, lay.in_dim[L - 1], logits, dz,

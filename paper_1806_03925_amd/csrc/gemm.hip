@@ -5,16 +5,19 @@
 //   dgrad     d_{l-1}  = (d_l W_l) * [a_{l-1} > 0]     NT on the transposed weight copy
 //   wgrad     dW_l     = d_l^T h_{l-1}                  TN, split over the batch, fixed-order sum
 //
-// One workgroup = 4 wavefronts (2 x 2) on a 256 x 128 block tile; a wavefront owns 128 x 64 as
-// 4 x 2 MFMA 32x32 tiles, so an operand fetched from LDS is used by two (A) or four (B) MFMAs.
-// bf16 operands use v_mfma_f32_32x32x16_bf16 (8 k-values per lane), fp32 operands
-// v_mfma_f32_32x32x2_f32; accumulation is fp32 in both.  Operand tiles sit in LDS as [row][k]
-// with k contiguous, so a lane fetches a bf16 MFMA operand with one 16-byte LDS read.  The next
-// k-tile is prefetched from global memory into registers while the current one is multiplied.
-// For the TN form the global tiles are [k][row]; a thread transposes 8 x 8 blocks in registers
-// on the way into LDS.  bf16 results leave through LDS so that every lane stores 16 contiguous
-// bytes.  Consecutive workgroup ids are spread over the eight XCDs by the hardware; the tile index
-// is remapped so that workgroups on one XCD walk neighbouring tiles and share operands in its L2.
+// bf16, K a multiple of 32 (every workload): one workgroup = 8 wavefronts (2 x 4) on a 256 x 256
+// block tile, a wavefront owns 128 x 64 as 4 x 2 MFMA 32x32x16 tiles.  Operand tiles of k-depth 32
+// are copied global -> LDS by DMA (global_load_lds_dwordx4) into four stages, two tiles in flight
+// while one is multiplied, one s_barrier per k-tile.  NT form: LDS rows are [row][32 k] with the four
+// 16-byte k-pieces XOR-swizzled by the row so that ds_read_b128 operand fetches do not conflict.
+// TN form (wgrad): LDS keeps the global [k][row] order and ds_read_b64_tr_b16 assembles the operand.
+// bf16 results leave through a per-wave LDS patch so that every lane stores 16 contiguous bytes.
+// Consecutive workgroup ids are spread over the eight XCDs by the hardware; the tile index is
+// remapped so that workgroups on one XCD walk neighbouring tiles and share operands in its L2.
+//
+// Everything else (fp32 operands with v_mfma_f32_32x32x2_f32, K not a multiple of 32) goes through a
+// register-staged kernel: 4 wavefronts on a 256 x 128 tile, operands in LDS as [row][k], the next
+// k-tile prefetched into registers, TN tiles transposed in registers on the way into LDS.
 #include "gear_internal.hpp"
 
 #include <type_traits>
@@ -807,9 +810,11 @@ hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, co
 
 }  // namespace
 
+// Split count of the wgrad contraction: one workgroup per CU holds a 256 x 256 tile, so aim at one
+// full round of the 256 CUs; every range keeps at least 512 rows of the batch.
 int gemm_splitk_for(int M, int N, int K) {
-  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  int s = (512 + tiles - 1) / tiles;
+  const int tiles = ((M + DM - 1) / DM) * ((N + DN - 1) / DN);
+  int s = 256 / tiles;
   int cap = K / 512;
   if (cap < 1) cap = 1;
   if (s > cap) s = cap;
