@@ -163,9 +163,9 @@ bool make_layout(const gear_config &c, Layout *lay) {
   const size_t tiles = (NNZ + kSortTile - 1) / kSortTile;
   lay->tile_units = take(&cur, tiles * sizeof(int32_t));
   lay->tile_emits = take(&cur, tiles * sizeof(int32_t));
-  lay->unit_q0 = take(&cur, NNZ * sizeof(int32_t));
-  lay->unit_slot = take(&cur, NNZ * sizeof(int32_t));
-  lay->unit_seg = take(&cur, NNZ * sizeof(int32_t));
+  lay->units = take(&cur, NNZ * sizeof(UnitDesc));
+  lay->row_view = take(&cur, NNZ * sizeof(int32_t));
+  lay->row_scale = take(&cur, NNZ * sizeof(float));
   lay->n_units = take(&cur, sizeof(int32_t));
   lay->total = cur;
   return true;
@@ -325,9 +325,9 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   AccumPlan plan;
   plan.tile_units = (int32_t *)(ws + lay.tile_units);
   plan.tile_emits = (int32_t *)(ws + lay.tile_emits);
-  plan.unit_q0 = (int32_t *)(ws + lay.unit_q0);
-  plan.unit_slot = (int32_t *)(ws + lay.unit_slot);
-  plan.unit_seg = (int32_t *)(ws + lay.unit_seg);
+  plan.units = (UnitDesc *)(ws + lay.units);
+  plan.row_view = (int32_t *)(ws + lay.row_view);
+  plan.row_scale = (float *)(ws + lay.row_scale);
   plan.n_units = (int32_t *)(ws + lay.n_units);
   // The grouping depends on the ids only: it runs on the helper stream while the main stream gathers
   // and runs the forward pass, and is joined before the first kernel that changes caller state.
@@ -340,7 +340,8 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
     hipStream_t s = side->stream;  // the two launches below go to the helper stream
     (void)main_stream;
     GEAR_RUN("group_ids", launch_group(gb, status, s));
-    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, counts, M, out->ready_cap, out->n_ready, status, s));
+    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap, out->n_ready,
+                                                   status, s));
   }
   GEAR_HIP(hipEventRecord(side->join, side->stream));
 
@@ -391,8 +392,8 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   GEAR_RUN("embedding_update",
            launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb,
                                    (float *)(ws + lay.emb_partial), lr, status, s));
-  GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, occ_view, b->img_off, dx, F, grad_accum, counts, M,
-                                           out->ready_ids, out->ready_grads, status, s));
+  GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx, F, grad_accum, M, out->ready_ids,
+                                           out->ready_grads, status, s));
   GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
 
   if (out->dbg_img_unique && b->nnz > 0)

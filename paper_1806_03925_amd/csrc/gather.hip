@@ -12,6 +12,8 @@
 namespace gear {
 namespace {
 
+constexpr int kMaxPieces = 2;
+
 template <typename ET, typename DT, typename XT>
 __global__ void __launch_bounds__(256)
 k_gather_pool(int B, int d, int D, const int32_t *__restrict__ user_id, const int32_t *__restrict__ url_id,
@@ -42,35 +44,61 @@ k_gather_pool(int B, int d, int D, const int32_t *__restrict__ user_id, const in
     }
   }
 
-  // mean of the view's DFV rows
+  // mean of the view's DFV rows: a lane owns up to kMaxPieces 16-byte pieces of the row (columns
+  // lane*DN + p*64*DN); the pieces of four rows are requested together, the sum runs in CSR order
   constexpr int DN = Vec16<DT>::N;
   const int lo = img_off[view], hi = img_off[view + 1];
   const float inv = hi > lo ? 1.0f / (float)(hi - lo) : 0.0f;
-  for (int col = lane * DN; col < D; col += kWave * DN) {
-    float acc[DN];
+  for (int col0 = 0; col0 < D; col0 += kMaxPieces * kWave * DN) {
+    float acc[kMaxPieces][DN];
 #pragma unroll
-    for (int e = 0; e < DN; ++e) acc[e] = 0.0f;
-    int j = lo;
-    for (; j + 4 <= hi; j += 4) {  // four rows in flight
-      Vec16<DT> v0, v1, v2, v3;
-      const int64_t i0 = img_id[j], i1 = img_id[j + 1], i2 = img_id[j + 2], i3 = img_id[j + 3];
-      v0.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i0 * D + col);
-      v1.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i1 * D + col);
-      v2.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i2 * D + col);
-      v3.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i3 * D + col);
+    for (int p = 0; p < kMaxPieces; ++p)
 #pragma unroll
-      for (int e = 0; e < DN; ++e) acc[e] = (((acc[e] + v0.get(e)) + v1.get(e)) + v2.get(e)) + v3.get(e);
+      for (int e = 0; e < DN; ++e) acc[p][e] = 0.0f;
+    for (int j = lo; j < hi; j += 4) {
+      Vec16<DT> v[4][kMaxPieces];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t id = j + r < hi ? img_id[j + r] : -1;
+#pragma unroll
+        for (int p = 0; p < kMaxPieces; ++p) {
+          const int col = col0 + (p * kWave + lane) * DN;
+          if (id >= 0 && col < D)
+            v[r][p].v = *reinterpret_cast<const decltype(v[r][p].v) *>(dfv + id * D + col);
+          else
+            v[r][p].v = decltype(v[r][p].v){};
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int p = 0; p < kMaxPieces; ++p)
+#pragma unroll
+          for (int e = 0; e < DN; ++e) acc[p][e] += v[r][p].get(e);
     }
-    for (; j < hi; ++j) {
-      Vec16<DT> v0;
-      const int64_t i0 = img_id[j];
-      v0.v = *reinterpret_cast<const decltype(v0.v) *>(dfv + i0 * D + col);
 #pragma unroll
-      for (int e = 0; e < DN; ++e) acc[e] += v0.get(e);
+    for (int p = 0; p < kMaxPieces; ++p) {
+      const int col = col0 + (p * kWave + lane) * DN;
+      if (col < D) {
+        XT *dst = xrow + 2 * d + col;
+        if constexpr (sizeof(XT) == 2) {
+          Vec16<XT> o;
+          o.v = decltype(o.v){};
+#pragma unroll
+          for (int e = 0; e < DN; ++e) o.set(e % 8, acc[p][e] * inv), (void)0;
+          if constexpr (DN == 8) {
+            *reinterpret_cast<uint4 *>(dst) = o.v;
+          } else {  // four values: half a vector
+            *reinterpret_cast<uint2 *>(dst) = make_uint2(o.v.x, o.v.y);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < DN; e += 4)
+            *reinterpret_cast<float4 *>(dst + e) =
+                make_float4(acc[p][e] * inv, acc[p][e + 1] * inv, acc[p][e + 2] * inv, acc[p][e + 3] * inv);
+        }
+      }
     }
-    XT *dst = xrow + 2 * d + col;
-#pragma unroll
-    for (int e = 0; e < DN; ++e) dst[e] = from_f32<XT>(acc[e] * inv);
   }
 }
 

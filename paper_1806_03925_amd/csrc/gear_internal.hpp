@@ -92,12 +92,21 @@ struct GroupBatch {
 };
 
 // plan of the windowed accumulation over the sorted image occurrences
+struct UnitDesc {         // one workgroup's share of the accumulation (32 bytes)
+  int32_t q0;             // first sorted position of the unit
+  int32_t image;          // image id
+  int32_t slot;           // ready-list slot of the unit's (first) emission
+  int32_t s0, s1;         // the image's range of sorted positions
+  int32_t phase;          // gradients already collected for the image before this step, modulo M
+  int32_t pad[2];
+};
+
 struct AccumPlan {
   int32_t *tile_units;   // [n_tiles] unit heads per tile
   int32_t *tile_emits;   // [n_tiles] completed groups per tile
-  int32_t *unit_q0;      // [nnz] first sorted position of a unit
-  int32_t *unit_slot;    // [nnz] ready-list slot of the unit's emission
-  int32_t *unit_seg;     // [nnz] segment (distinct image) the unit belongs to
+  UnitDesc *units;       // [nnz]
+  int32_t *row_view;     // [nnz] view that owns the occurrence at each sorted position
+  float *row_scale;      // [nnz] 1 / (images of that view): backward of the mean
   int32_t *n_units;      // [1]
 };
 
@@ -122,7 +131,7 @@ struct Layout {
   struct G {
     size_t keys[2], vals[2], block_hist, tile_heads, unique, segoff, pos_seg, n_unique;
   } g[kMaxProblems];
-  size_t tile_units, tile_emits, unit_q0, unit_slot, unit_seg, n_units;
+  size_t tile_units, tile_emits, units, row_view, row_scale, n_units;
   size_t total;
 };
 
@@ -144,8 +153,9 @@ hipError_t launch_validate(const gear_config &cfg, const gear_batch &b, int32_t 
                            hipStream_t s);
 
 hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t s);
-hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *counts, int32_t M,
-                             int32_t ready_cap, int32_t *n_ready, int32_t *status, hipStream_t s);
+hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *occ_view,
+                             const int32_t *img_off, const int32_t *counts, int32_t M, int32_t ready_cap,
+                             int32_t *n_ready, int32_t *status, hipStream_t s);
 
 hipError_t launch_gather_pool(const gear_config &cfg, const gear_batch &b, const gear_tables &t,
                               const void *dfv_cache, void *x, const int32_t *status, hipStream_t s);
@@ -181,10 +191,9 @@ hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &u
                                    const int32_t *status, hipStream_t s);
 size_t embedding_partial_floats(const gear_config &cfg);
 
-hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan,
-                             const int32_t *occ_view, const int32_t *img_off, const float *dx, int F,
-                             float *grad_accum, const int32_t *counts, int32_t M, int32_t *ready_ids,
-                             float *ready_grads, const int32_t *status, hipStream_t s);
+hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan, const float *dx,
+                             int F, float *grad_accum, int32_t M, int32_t *ready_ids, float *ready_grads,
+                             const int32_t *status, hipStream_t s);
 hipError_t launch_count_update(const GroupProblem &img, int32_t *counts, const int32_t *status, hipStream_t s);
 
 hipError_t launch_refresh(int dtype, void *dfv_cache, int64_t n_images, int dim, const int32_t *ids,

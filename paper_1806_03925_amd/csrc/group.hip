@@ -289,8 +289,11 @@ __global__ void __launch_bounds__(kSortBlock) k_plan_count(GroupProblem p, Accum
   }
 }
 
-__global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, AccumPlan plan, const int32_t *counts,
-                                                             int M, int ready_cap, int32_t *n_ready, int32_t *status) {
+__global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, AccumPlan plan,
+                                                             const int32_t *__restrict__ occ_view,
+                                                             const int32_t *__restrict__ img_off,
+                                                             const int32_t *counts, int M, int ready_cap,
+                                                             int32_t *n_ready, int32_t *status) {
   if (*status != 0) return;
   const int tile0 = blockIdx.x * kSortTile;
   if (p.n <= 0) {
@@ -321,10 +324,22 @@ __global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, Acc
   for (int i = 0; i < kSortItems; ++i) {
     const int q = tile0 + threadIdx.x * kSortItems + i;
     if (q < p.n) {
+      // where the occurrence's gradient lives: dLoss/dx of its view, divided by the view's image count
+      const int view = occ_view[p.perm[q]];
+      plan.row_view[q] = view;
+      plan.row_scale[q] = 1.0f / (float)(img_off[view + 1] - img_off[view]);
       if (f[i].unit) {
-        plan.unit_q0[u] = q;
-        plan.unit_slot[u] = e;
-        plan.unit_seg[u] = p.pos_seg[q];
+        const int seg = p.pos_seg[q];
+        const int image = p.sorted_keys[q];
+        UnitDesc d;
+        d.q0 = q;
+        d.image = image;
+        d.slot = e;
+        d.s0 = p.segoff[seg];
+        d.s1 = p.segoff[seg + 1];
+        d.phase = counts[image] % M;
+        d.pad[0] = d.pad[1] = 0;
+        plan.units[u] = d;
         ++u;
       }
       if (f[i].emit) ++e;
@@ -357,13 +372,14 @@ hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *counts, int32_t M,
-                             int32_t ready_cap, int32_t *n_ready, int32_t *status, hipStream_t s) {
+hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *occ_view,
+                             const int32_t *img_off, const int32_t *counts, int32_t M, int32_t ready_cap,
+                             int32_t *n_ready, int32_t *status, hipStream_t s) {
   int tiles = (img.n + kSortTile - 1) / kSortTile;
   if (tiles < 1) tiles = 1;
   hipLaunchKernelGGL(k_plan_count, dim3(tiles), dim3(kSortBlock), 0, s, img, plan, counts, M, status);
-  hipLaunchKernelGGL(k_plan_scatter, dim3(tiles), dim3(kSortBlock), 0, s, img, plan, counts, M, ready_cap, n_ready,
-                     status);
+  hipLaunchKernelGGL(k_plan_scatter, dim3(tiles), dim3(kSortBlock), 0, s, img, plan, occ_view, img_off, counts, M,
+                     ready_cap, n_ready, status);
   return hipGetLastError();
 }
 
