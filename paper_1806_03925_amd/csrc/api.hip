@@ -357,35 +357,45 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   for (int l = 0; l < L - 1; ++l)
     GEAR_RUN(kFwd[l], launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l],
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
-                                     ws + lay.h[l], status, s));
+                                     ws + lay.h[l], nullptr, status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
   GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
   GEAR_RUN("logit_loss_sgd",
            launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.w_off[L - 1],
-                             t->mlp_params + lay.b_off[L - 1], b->label, B, lay.in_dim[L - 1], logits, dz,
-                             ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial), out->loss, lr, status, s));
+                             t->mlp_params + lay.b_off[L - 1], t->mlp_params + lay.b_off[L - 2], b->label, B,
+                             lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial),
+                             out->loss, lr, status, s));
 
   // backward through the hidden layers down to dLoss/dx (all from the pre-step operand copies)
+  // Each product that makes the delta of a hidden layer also leaves that layer's bias gradient (column
+  // sums of the delta) as per-row-tile partials, which are added in tile order and applied at once.
   float *dx = (float *)(ws + lay.dx);
+  float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
   for (int l = L - 2; l >= 0; --l) {
-    if (l > 0)
+    if (l > 0) {
+      const int parts = gemm_nt_colsum_parts(dt, B, lay.in_dim[l], lay.out_dim[l]);
       GEAR_RUN(kDgrad[l], launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l],
-                                         EPI_MASK, nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1], status, s));
-    else
+                                         EPI_MASK, nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1],
+                                         parts ? cpart : nullptr, status, s));
+      if (parts)
+        GEAR_RUN("bias_sgd", launch_partial_sgd(cpart, parts, lay.out_dim[l - 1], t->mlp_params + lay.b_off[l - 1], lr,
+                                                status, s));
+      else
+        GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l - 1], B, lay.out_dim[l - 1], cpart,
+                                               t->mlp_params + lay.b_off[l - 1], lr, status, s));
+    } else {
       GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_F32,
-                                         nullptr, nullptr, dx, status, s));
+                                         nullptr, nullptr, dx, nullptr, status, s));
+    }
   }
 
-  // SGD on the hidden layers: split-K wgrad and bias column sums (the logit layer was done above)
-  float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
+  // SGD on the hidden layers' weights: split-K wgrad (logit layer and all biases are done above)
   for (int l = L - 2; l >= 0; --l) {
     const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
     GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
                                               lay.in_dim[l], B, splits, wpart, status, s));
     GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
                                              t->mlp_params + lay.w_off[l], lr, status, s));
-    GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l], B, lay.out_dim[l], cpart,
-                                           t->mlp_params + lay.b_off[l], lr, status, s));
   }
 
   // SGD on the touched embedding rows, then the per-image gradient bookkeeping
@@ -457,7 +467,7 @@ gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B,
     if (K % vec || N % vec || epilogue < EPI_BIAS_RELU || epilogue > EPI_F32) return GEAR_ERR_INVALID;
     if ((epilogue == EPI_BIAS_RELU && !bias) || (epilogue == EPI_MASK && (!aux || !aligned16(aux))))
       return GEAR_ERR_INVALID;
-    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, status, s));
+    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, nullptr, status, s));
   } else if (form == 1) {
     if (M % vec || N % vec || splits < 1 || splits > 64 || !partial) return GEAR_ERR_INVALID;
     GEAR_HIP(launch_gemm_tn_splitk(dtype, A, B, M, N, K, splits, partial, status, s));

@@ -170,7 +170,12 @@ enum GemmEpilogue {
 };
 // C[M x N] = A[M x K] * B[N x K]^T, both operands K-contiguous, type `dtype`.
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue,
-                          const float *bias, const void *aux, void *out, const int32_t *status, hipStream_t s);
+                          const float *bias, const void *aux, void *out, float *colpart, const int32_t *status,
+                          hipStream_t s);
+int gemm_nt_colsum_parts(int dtype, int M, int N, int K);
+// dst[j] -= lr * sum_p partial[p][j], p ascending in a fixed two-level shape
+hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, float lr, const int32_t *status,
+                              hipStream_t s);
 // partial[z][M x N] = sum over the z-th K range of A[K x M]^T * B[K x N] (operands M-/N-contiguous).
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
                                  float *partial, const int32_t *status, hipStream_t s);
@@ -179,8 +184,9 @@ hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, fl
                              const int32_t *status, hipStream_t s);
 
 hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
-                             const float *label, int B, int H, float *logits, float *dz, void *delta,
-                             float *partials, float *loss, float lr, const int32_t *status, hipStream_t s);
+                             float *bias_hidden, const float *label, int B, int H, float *logits, float *dz,
+                             void *delta, float *partials, float *loss, float lr, const int32_t *status,
+                             hipStream_t s);
 size_t logit_partial_floats(int H);
 
 hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, float lr,

@@ -377,7 +377,8 @@ __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_ad
 template <int EPI>
 __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
                                                int wn, int lane, int M, int N, const float *__restrict__ bias,
-                                               const bf16_t *__restrict__ aux, void *__restrict__ out) {
+                                               const bf16_t *__restrict__ aux, void *__restrict__ out,
+                                               float (&colacc)[8]) {
   const int c = lane & 31, g = lane >> 5;
   float bn[TN];
 #pragma unroll
@@ -428,6 +429,9 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
               if (lo != 0u && lo < 0x8000u) keep |= 0x0000ffffu;
               if (hi != 0u && hi < 0x8000u) keep |= 0xffff0000u;
               v.w[w] &= keep;
+              // column sums of what is stored (the bias gradient of the layer below)
+              colacc[2 * w] += __uint_as_float(v.w[w] << 16);
+              colacc[2 * w + 1] += __uint_as_float(v.w[w] & 0xffff0000u);
             }
           }
           *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(out) + idx) = v.u;
@@ -445,7 +449,7 @@ template <int EPI>
 __global__ void __launch_bounds__(DTHREADS)
 k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K,
               const float *__restrict__ bias, const bf16_t *__restrict__ aux, void *__restrict__ out,
-              const int32_t *__restrict__ status) {
+              float *__restrict__ colpart, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[STAGES * STAGE_ELEMS];   // [stage][A tile | B tile]
 
@@ -510,7 +514,31 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
   wait_vm<0>();
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
   bf16_t *patch = lds + wave * 32 * WN;
-  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out);
+  float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, colacc);
+  if constexpr (EPI == EPI_MASK) {
+    if (colpart) {
+      // colpart[m-tile][n] = sum over the tile's rows of the stored values: lanes that share lane % 8
+      // hold the same eight columns, then the two waves that share the columns are added
+      float *s_col = reinterpret_cast<float *>(lds + 8 * 32 * WN);  // behind the eight output patches
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = colacc[e];
+        v += __shfl_xor(v, 8, kWave);
+        v += __shfl_xor(v, 16, kWave);
+        v += __shfl_xor(v, 32, kWave);
+        if (lane < 8) s_col[wave * 64 + lane * 8 + e] = v;
+      }
+      __syncthreads();
+      if (wm == 0 && lane < 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int n = n0 + wn * WN + lane * 8 + e;
+          if (n < N) colpart[(size_t)(m0 / DM) * N + n] = s_col[wave * 64 + lane * 8 + e] + s_col[(wave + 4) * 64 + lane * 8 + e];
+        }
+      }
+    }
+  }
 }
 
 // ---- TN form (wgrad), bf16, by DMA and LDS transpose reads ---------------------------------------
@@ -584,10 +612,14 @@ k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
+  // one-dimensional grid of tiles x k-ranges; the workgroups of one XCD take neighbouring (range, tile)
+  // pairs, so the tiles that read the same rows of the batch share them in that XCD's L2
   const int n_tiles = (N + DN - 1) / DN;
-  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int tiles = ((M + DM - 1) / DM) * n_tiles;
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int split = work / tiles, tile = work % tiles;
   const int m0 = (tile / n_tiles) * DM, n0 = (tile % n_tiles) * DN;
-  const int k_begin = blockIdx.z * k_chunk;
+  const int k_begin = split * k_chunk;
   const int k_end = min(K, k_begin + k_chunk);
 
   // DMA: chunk c = k-rows 2c, 2c+1; lane p holds LDS slot p%32 of k-row p/32, which receives the
@@ -649,7 +681,7 @@ k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
     stage = (stage + 1) & 3;
   }
   // fp32 partial of this k range
-  float *dst = partial + (size_t)blockIdx.z * M * N;
+  float *dst = partial + (size_t)split * M * N;
   const int c = lane & 31, g = lane >> 5;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -776,14 +808,14 @@ __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ pa
 
 template <typename T>
 hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, const float *bias, const void *aux,
-                  void *out, const int32_t *status, hipStream_t s) {
+                  void *out, float *colpart, const int32_t *status, hipStream_t s) {
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
   if constexpr (sizeof(T) == 2) {
     if (K % DK == 0) {
       const dim3 grid(((M + DM - 1) / DM) * ((N + DN - 1) / DN));
 #define GEAR_DMA(E)                                                                                               \
   hipLaunchKernelGGL((k_gemm_nt_dma<E>), grid, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, \
-                     bias, (const bf16_t *)aux, out, status)
+                     bias, (const bf16_t *)aux, out, colpart, status)
       if (epi == EPI_BIAS_RELU)
         GEAR_DMA(EPI_BIAS_RELU);
       else if (epi == EPI_MASK)
@@ -822,11 +854,18 @@ int gemm_splitk_for(int M, int N, int K) {
   return s < 1 ? 1 : s;
 }
 
+// Number of row-tile partials the EPI_MASK product leaves in `colpart` ([parts x N] column sums of
+// its result), or 0 if this shape goes through the kernel that does not produce them.
+int gemm_nt_colsum_parts(int dtype, int M, int N, int K) {
+  return (dtype == GEAR_BF16 && K % DK == 0 && M > 0) ? (M + DM - 1) / DM : 0;
+}
+
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue_kind,
-                          const float *bias, const void *aux, void *out, const int32_t *status, hipStream_t s) {
+                          const float *bias, const void *aux, void *out, float *colpart, const int32_t *status,
+                          hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  return dtype == GEAR_BF16 ? run_nt<bf16_t>(A, B, M, N, K, epilogue_kind, bias, aux, out, status, s)
-                            : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, status, s);
+  return dtype == GEAR_BF16 ? run_nt<bf16_t>(A, B, M, N, K, epilogue_kind, bias, aux, out, colpart, status, s)
+                            : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, colpart, status, s);
 }
 
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
@@ -838,7 +877,7 @@ hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M,
   if (k_chunk == 0) k_chunk = bk;
   if (dtype == GEAR_BF16 && K % DK == 0 && M >= 8 && N >= 8) {
     const int kc = ((((K + splits - 1) / splits) + DK - 1) / DK) * DK;
-    const dim3 grid_dma(((M + DM - 1) / DM) * ((N + DN - 1) / DN), 1, splits);
+    const dim3 grid_dma(((M + DM - 1) / DM) * ((N + DN - 1) / DN) * splits);
     hipLaunchKernelGGL(k_gemm_tn_dma, grid_dma, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, kc,
                        partial, status);
     return hipGetLastError();

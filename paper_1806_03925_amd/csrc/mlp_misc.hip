@@ -46,28 +46,30 @@ constexpr int kMaxVecPerLane = 4;  // a lane owns up to 4 16-byte pieces of a ro
 //   z = h . w + b,  loss term,  dz = (sigmoid(z) - y) / B,
 //   delta[b, j] = dz * w[j] * [h[b, j] > 0]                      (delta of the last hidden layer)
 //   part_w[block][j] = sum_b dz_b h[b, j],  part_b[block] = sum_b dz_b,  part_loss[block] = sum_b loss_b
+//   part_d[block][j] = sum_b delta[b, j]                         (bias gradient of the last hidden layer)
 template <typename T>
 __global__ void __launch_bounds__(256)
 k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__restrict__ bias,
              const float *__restrict__ label, int B, int H, int rows_per_block, float *__restrict__ logits,
              float *__restrict__ dz_out, T *__restrict__ delta, float *__restrict__ part_w,
-             float *__restrict__ part_b, float *__restrict__ part_loss, const int32_t *__restrict__ status) {
+             float *__restrict__ part_d, float *__restrict__ part_b, float *__restrict__ part_loss,
+             const int32_t *__restrict__ status) {
   if (*status != 0) return;
   constexpr int VEC = Vec16<T>::N;
   __shared__ float s_red[4][2];
-  extern __shared__ float s_w[];  // [4][H] per-wave weight-gradient sums
+  extern __shared__ float s_w[];  // [4][H] per-wave weight-gradient sums, then [4][H] delta sums
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_vec = H / VEC;
   const float b0 = bias[0], invB = 1.0f / (float)B;
 
   Vec16<T> wv[kMaxVecPerLane];
-  float gw[kMaxVecPerLane][VEC];
+  float gw[kMaxVecPerLane][VEC], gd[kMaxVecPerLane][VEC];
 #pragma unroll
   for (int i = 0; i < kMaxVecPerLane; ++i) {
     const int v = lane + i * kWave;
     if (v < n_vec) wv[i].v = *reinterpret_cast<const decltype(wv[i].v) *>(w + v * VEC);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) gw[i][e] = 0.0f;
+    for (int e = 0; e < VEC; ++e) gw[i][e] = gd[i][e] = 0.0f;
   }
   float loss_acc = 0.0f, dz_acc = 0.0f;
   const int r0 = blockIdx.x * rows_per_block, r1 = min(B, r0 + rows_per_block);
@@ -106,6 +108,7 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
           const float hval = hv[i].get(e);
           gw[i][e] += dz * hval;
           dv.set(e, hval > 0.0f ? dz * wv[i].get(e) : 0.0f);
+          gd[i][e] += dv.get(e);  // the stored (rounded) value
         }
         *reinterpret_cast<decltype(dv.v) *>(dr + v * VEC) = dv.v;
       }
@@ -117,15 +120,20 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
     const int v = lane + i * kWave;
     if (v < n_vec)
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) s_w[wave * H + v * VEC + e] = gw[i][e];
+      for (int e = 0; e < VEC; ++e) {
+        s_w[wave * H + v * VEC + e] = gw[i][e];
+        s_w[(4 + wave) * H + v * VEC + e] = gd[i][e];
+      }
   }
   if (lane == 0) {
     s_red[wave][0] = loss_acc;
     s_red[wave][1] = dz_acc;
   }
   __syncthreads();
-  for (int j = threadIdx.x; j < H; j += blockDim.x)
+  for (int j = threadIdx.x; j < H; j += blockDim.x) {
     part_w[(size_t)blockIdx.x * H + j] = ((s_w[j] + s_w[H + j]) + s_w[2 * H + j]) + s_w[3 * H + j];
+    part_d[(size_t)blockIdx.x * H + j] = ((s_w[4 * H + j] + s_w[5 * H + j]) + s_w[6 * H + j]) + s_w[7 * H + j];
+  }
   if (threadIdx.x == 0) {
     part_loss[blockIdx.x] = ((s_red[0][0] + s_red[1][0]) + s_red[2][0]) + s_red[3][0];
     part_b[blockIdx.x] = ((s_red[0][1] + s_red[1][1]) + s_red[2][1]) + s_red[3][1];
@@ -135,8 +143,15 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
 __global__ void __launch_bounds__(64) k_loss_final(const float *__restrict__ loss_partial, int n, int B,
                                                    float *__restrict__ loss, const int32_t *__restrict__ status) {
   if (*status != 0) return;
+  float part[kLossBlocks / kWave];
+#pragma unroll
+  for (int k = 0; k < kLossBlocks / kWave; ++k) {
+    const int i = threadIdx.x + k * kWave;
+    part[k] = i < n ? loss_partial[i] : 0.0f;
+  }
   float v = 0.0f;
-  for (int i = threadIdx.x; i < n; i += kWave) v += loss_partial[i];
+#pragma unroll
+  for (int k = 0; k < kLossBlocks / kWave; ++k) v += part[k];
   v = wave_sum(v);
   if (threadIdx.x == 0) *loss = v / (float)B;
 }
@@ -227,28 +242,38 @@ int logit_blocks(int B) {
 
 // Forward logit + loss + delta of the last hidden layer, then SGD on the logit layer's weight and bias.
 hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
-                             const float *label, int B, int H, float *logits, float *dz, void *delta,
-                             float *partials, float *loss, float lr, const int32_t *status, hipStream_t s) {
+                             float *bias_hidden, const float *label, int B, int H, float *logits, float *dz,
+                             void *delta, float *partials, float *loss, float lr, const int32_t *status,
+                             hipStream_t s) {
   if (B <= 0) return hipSuccess;
   const int blocks = logit_blocks(B);
   const int rows_per_block = (B + blocks - 1) / blocks;
-  float *part_w = partials, *part_b = partials + (size_t)kLossBlocks * H, *part_loss = part_b + kLossBlocks;
-  const size_t smem = 4 * (size_t)H * sizeof(float);
+  float *part_w = partials, *part_d = part_w + (size_t)kLossBlocks * H, *part_b = part_d + (size_t)kLossBlocks * H,
+        *part_loss = part_b + kLossBlocks;
+  const size_t smem = 8 * (size_t)H * sizeof(float);
   if (dtype == GEAR_BF16)
     hipLaunchKernelGGL(k_logit_loss<bf16_t>, dim3(blocks), dim3(256), smem, s, (const bf16_t *)h,
                        (const bf16_t *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz, (bf16_t *)delta,
-                       part_w, part_b, part_loss, status);
+                       part_w, part_d, part_b, part_loss, status);
   else
     hipLaunchKernelGGL(k_logit_loss<float>, dim3(blocks), dim3(256), smem, s, (const float *)h,
                        (const float *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz, (float *)delta,
-                       part_w, part_b, part_loss, status);
+                       part_w, part_d, part_b, part_loss, status);
   hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, s, part_loss, blocks, B, loss, status);
   hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, part_w, blocks, H, w_last, lr, status);
   hipLaunchKernelGGL(k_partial_sgd, dim3(1), dim3(256), 0, s, part_b, blocks, 1, bias_last, lr, status);
+  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, part_d, blocks, H, bias_hidden, lr, status);
   return hipGetLastError();
 }
 
-size_t logit_partial_floats(int H) { return (size_t)kLossBlocks * H + 2 * (size_t)kLossBlocks; }
+size_t logit_partial_floats(int H) { return 2 * (size_t)kLossBlocks * H + 2 * (size_t)kLossBlocks; }
+
+hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, float lr, const int32_t *status,
+                              hipStream_t s) {
+  if (P <= 0 || H <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, partial, P, H, dst, lr, status);
+  return hipGetLastError();
+}
 
 // dst[j] -= lr * sum_b src[b][j]   (bias gradient of a hidden layer)
 hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, float lr,
