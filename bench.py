@@ -69,7 +69,7 @@ class WorkModel:
         work["gather_pool"] = ("hbm", 12.0 * B + 4.0 * nnz + (uu + ul) * d * e_emb + len(img) * D * e_dfv
                                + B * F * e_act)
         work["embedding_update"] = ("hbm", 16.0 * B + 2.0 * B * d * 4 + 2.0 * (uu + ul) * d * e_emb)
-        work["accumulate"] = ("hbm", 12.0 * nnz + with_img * D * 4.0 + int((p != 0).sum()) * D * 4.0
+        work["accumulate"] = ("hbm", 40.0 * len(img) + 8.0 * nnz + with_img * D * e_act + int((p != 0).sum()) * D * 4.0
                               + int(((final != 0) | (p != 0)).sum()) * D * 4.0 + emits * D * 4.0)
         return work
 

@@ -118,7 +118,9 @@ int64_t gear_mlp_param_count(const gear_config *cfg);
 int64_t gear_mlp_param_offset(const gear_config *cfg, int32_t layer, int32_t which);
 
 /* Byte offset and size, inside the workspace, of an intermediate of the last gear_step, for
- * inspection by tests: "x" [B x F] mlp_dtype, "logits" [B] f32, "dx" [B x F] f32 (dLoss/dx).
+ * inspection by tests: "x" [max_batch x F] mlp_dtype, "logits" [max_batch] f32, and dLoss/dx in two
+ * pieces: "dx_emb" [max_batch x 2*emb_dim] f32 (user and URL slots) and "dx_dfv" [max_batch x dfv_dim]
+ * in mlp_dtype (the DFV slot).
  * Returns GEAR_ERR_INVALID for an unknown name. */
 gear_status gear_workspace_region(const gear_config *cfg, const char *name, size_t *offset, size_t *bytes);
 

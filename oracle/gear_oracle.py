@@ -21,7 +21,7 @@ an MLP with ReLU hidden layers and one logit, sigmoid cross-entropy averaged
 over the batch, plain SGD.
 
 Arithmetic is fp64.  `round_to` is applied only where a workload *stores* a
-value in a narrower type (tables, bf16 MLP operands); see `Precision`.
+value in a narrower type (tables, bf16 MLP operands and deltas); see `Precision`.
 """
 from __future__ import annotations
 
@@ -273,7 +273,10 @@ class GearOracle:
                 # hidden deltas are MLP operands: ReLU mask, then operand rounding
                 delta = round_to(np.where(active[l], back, 0.0), self.prec.mlp)
             else:
-                dx = back                                            # kept unrounded
+                # dLoss/dx is the delta of the input layer: its DFV slot is kept in the operand type
+                # like the other deltas, the two embedding slots stay unrounded
+                dx = back
+                dx[:, 2 * d:] = round_to(dx[:, 2 * d:], self.prec.mlp)
 
         # 4. Apply the Sparse Part's gradients (plain SGD on MLP and on the touched rows).
         self.mlp = [(round_to(W - lr * dW, self.prec.master), round_to(b - lr * db, self.prec.master))

@@ -233,13 +233,18 @@ class GearState:
 
     def region(self, name: str, B: int) -> torch.Tensor:
         """An intermediate of the last step, read out of the workspace (tests only)."""
+        if name == "dx":
+            return torch.cat([self.region("dx_emb", B), self.region("dx_dfv", B).float()], dim=1)
         off, size = gear_workspace_region(self.cfg, name)
         raw = self.workspace[off:off + size]
         F = 2 * self.cfg.emb_dim + self.cfg.dfv_dim
+        d, D = self.cfg.emb_dim, self.cfg.dfv_dim
         if name == "x":
             return raw.view(TORCH_DTYPE[self.cfg.mlp_dtype])[:B * F].view(B, F)
-        if name == "dx":
-            return raw.view(torch.float32)[:B * F].view(B, F)
+        if name == "dx_emb":
+            return raw.view(torch.float32)[:B * 2 * d].view(B, 2 * d)
+        if name == "dx_dfv":
+            return raw.view(TORCH_DTYPE[self.cfg.mlp_dtype])[:B * D].view(B, D)
         return raw.view(torch.float32)[:B]
 
 

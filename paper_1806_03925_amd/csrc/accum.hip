@@ -2,7 +2,8 @@
 //
 // Section 3, step 5: every occurrence of an image in a page view yields (image id, dLoss/dDFV);
 // with mean pooling that gradient is dLoss/dx of the view's DFV slot divided by the view's image
-// count (Eq. 1, left factor).  Section 1, third point and Section 3, step 6: all gradients of an
+// count (Eq. 1, left factor).  For a bf16 MLP that slot is kept in bf16 like every other delta of the
+// network; sums, accumulators and emitted averages are fp32.  Section 1, third point and Section 3, step 6: all gradients of an
 // image are kept until M have arrived; their average is then handed on and collecting starts
 // afresh.  Keeping the running sum of an unfinished group in grad_accum[image] is the same thing
 // as keeping the gradients themselves, because only their sum is ever used.
@@ -14,10 +15,50 @@
 namespace gear {
 namespace {
 
+// A thread owns kCols<GT> consecutive columns: 16 bytes of a dLoss/dx row (4 fp32 or 8 bf16 values).
+template <typename GT> struct Cols;
+template <> struct Cols<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void load(const float *p, float (&v)[4]) {
+    const float4 t = *reinterpret_cast<const float4 *>(p);
+    v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+  }
+};
+template <> struct Cols<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[8]) {
+    const uint4 t = *reinterpret_cast<const uint4 *>(p);
+    v[0] = __uint_as_float(t.x << 16), v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16), v[3] = __uint_as_float(t.y & 0xffff0000u);
+    v[4] = __uint_as_float(t.z << 16), v[5] = __uint_as_float(t.z & 0xffff0000u);
+    v[6] = __uint_as_float(t.w << 16), v[7] = __uint_as_float(t.w & 0xffff0000u);
+  }
+};
+
+template <int N> __device__ __forceinline__ void load_f32(const float *p, float (&v)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; k += 4) {
+    const float4 t = *reinterpret_cast<const float4 *>(p + k);
+    v[k] = t.x, v[k + 1] = t.y, v[k + 2] = t.z, v[k + 3] = t.w;
+  }
+}
+template <int N> __device__ __forceinline__ void store_f32(float *p, const float (&v)[N], float scale) {
+#pragma unroll
+  for (int k = 0; k < N; k += 4)
+    *reinterpret_cast<float4 *>(p + k) = make_float4(v[k] * scale, v[k + 1] * scale, v[k + 2] * scale, v[k + 3] * scale);
+}
+template <int N> __device__ __forceinline__ void store_div(float *p, const float (&v)[N], float by) {
+#pragma unroll
+  for (int k = 0; k < N; k += 4)
+    *reinterpret_cast<float4 *>(p + k) = make_float4(v[k] / by, v[k + 1] / by, v[k + 2] / by, v[k + 3] / by);
+}
+
 // acc += sum over sorted positions [qa, qb) of dx[view(q)][col ..] / n_view, in order; eight rows in flight
-__device__ __forceinline__ void add_rows(float4 &acc, const int32_t *__restrict__ row_view,
-                                         const float *__restrict__ row_scale, const float *__restrict__ col, int F,
+template <typename GT>
+__device__ __forceinline__ void add_rows(float (&acc)[Cols<GT>::N], const int32_t *__restrict__ row_view,
+                                         const float *__restrict__ row_scale, const GT *__restrict__ col, int D,
                                          int qa, int qb) {
+  constexpr int N = Cols<GT>::N;
   for (int q = qa; q < qb; q += 8) {
     int view[8];
     float scale[8];
@@ -27,63 +68,84 @@ __device__ __forceinline__ void add_rows(float4 &acc, const int32_t *__restrict_
       view[i] = in ? row_view[q + i] : -1;
       scale[i] = in ? row_scale[q + i] : 0.0f;
     }
-    float4 v[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      v[i] = view[i] >= 0 ? *reinterpret_cast<const float4 *>(col + (size_t)view[i] * F) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float v[8][N];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      acc.x += v[i].x * scale[i];
-      acc.y += v[i].y * scale[i];
-      acc.z += v[i].z * scale[i];
-      acc.w += v[i].w * scale[i];
+      if (view[i] >= 0) {
+        Cols<GT>::load(col + (size_t)view[i] * D, v[i]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) v[i][k] = 0.0f;
+      }
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[k] += v[i][k] * scale[i];
   }
 }
 
+// dx: the DFV slot of dLoss/dx, [B x D].  One workgroup per unit, D / Cols<GT>::N threads.
+template <typename GT>
 __global__ void __launch_bounds__(256)
-k_accumulate(AccumPlan plan, const float *__restrict__ dx, int F, int col0, int D, float *__restrict__ accum, int M,
+k_accumulate(AccumPlan plan, const GT *__restrict__ dx, int D, float *__restrict__ accum, int M,
              int32_t *__restrict__ ready_ids, float *__restrict__ ready_grads, const int32_t *__restrict__ status) {
   if (*status != 0) return;
+  constexpr int N = Cols<GT>::N;
   const int n_units = *plan.n_units;
-  const int D4 = D / 4;
+  const int DC = D / N;
   const float fM = (float)M;
-  for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
-    const UnitDesc d = plan.units[u];
+  int u = blockIdx.x;
+  if (u >= n_units) return;
+  UnitDesc d = plan.units[u];
+  while (true) {
+    const int u_next = u + gridDim.x;
+    UnitDesc d_next = d;
+    if (u_next < n_units) d_next = plan.units[u_next];  // in flight while this unit is summed
     float *arow = accum + (size_t)d.image * D;
-    for (int c4 = threadIdx.x; c4 < D4; c4 += blockDim.x) {
-      const float *col = dx + col0 + 4 * c4;
-      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int cg = threadIdx.x; cg < DC; cg += blockDim.x) {
+      const GT *col = dx + N * cg;
+      float acc[N];
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[k] = 0.0f;
       if (d.q0 == d.s0) {
         // first group of this image in this step: continues what earlier steps left
         const int p = d.phase;
         const int len0 = min(M - p, d.s1 - d.s0);
-        if (p != 0) acc = *reinterpret_cast<const float4 *>(arow + 4 * c4);
-        add_rows(acc, plan.row_view, plan.row_scale, col, F, d.s0, d.s0 + len0);
+        if (p != 0) load_f32<N>(arow + N * cg, acc);
+        add_rows<GT>(acc, plan.row_view, plan.row_scale, col, D, d.s0, d.s0 + len0);
         const bool complete = (p + len0 == M);
         if (complete) {
-          *reinterpret_cast<float4 *>(ready_grads + (size_t)d.slot * D + 4 * c4) =
-              make_float4(acc.x / fM, acc.y / fM, acc.z / fM, acc.w / fM);
-          if (c4 == 0) ready_ids[d.slot] = d.image;
+          store_div<N>(ready_grads + (size_t)d.slot * D + N * cg, acc, fM);
+          if (cg == 0) ready_ids[d.slot] = d.image;
         }
         const int tail = (d.s1 - d.s0 - len0) % M;  // rows of the image's unfinished last group
         if (!complete) {
-          *reinterpret_cast<float4 *>(arow + 4 * c4) = acc;
+          store_f32<N>(arow + N * cg, acc, 1.0f);
         } else if (tail == 0) {
-          if (p != 0) *reinterpret_cast<float4 *>(arow + 4 * c4) = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (p != 0) {
+            float zero[N];
+#pragma unroll
+            for (int k = 0; k < N; ++k) zero[k] = 0.0f;
+            store_f32<N>(arow + N * cg, zero, 1.0f);
+          }
         } else {
-          float4 rest = make_float4(0.f, 0.f, 0.f, 0.f);
-          add_rows(rest, plan.row_view, plan.row_scale, col, F, d.s1 - tail, d.s1);
-          *reinterpret_cast<float4 *>(arow + 4 * c4) = rest;
+          float rest[N];
+#pragma unroll
+          for (int k = 0; k < N; ++k) rest[k] = 0.0f;
+          add_rows<GT>(rest, plan.row_view, plan.row_scale, col, D, d.s1 - tail, d.s1);
+          store_f32<N>(arow + N * cg, rest, 1.0f);
         }
       } else {
         // a complete middle group of M rows
-        add_rows(acc, plan.row_view, plan.row_scale, col, F, d.q0, d.q0 + M);
-        *reinterpret_cast<float4 *>(ready_grads + (size_t)d.slot * D + 4 * c4) =
-            make_float4(acc.x / fM, acc.y / fM, acc.z / fM, acc.w / fM);
-        if (c4 == 0) ready_ids[d.slot] = d.image;
+        add_rows<GT>(acc, plan.row_view, plan.row_scale, col, D, d.q0, d.q0 + M);
+        store_div<N>(ready_grads + (size_t)d.slot * D + N * cg, acc, fM);
+        if (cg == 0) ready_ids[d.slot] = d.image;
       }
     }
+    if (u_next >= n_units) break;
+    u = u_next;
+    d = d_next;
   }
 }
 
@@ -115,16 +177,21 @@ __global__ void __launch_bounds__(256) k_refresh(uint4 *__restrict__ cache, int6
 
 }  // namespace
 
-hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan, const float *dx,
-                             int F, float *grad_accum, int32_t M, int32_t *ready_ids, float *ready_grads,
-                             const int32_t *status, hipStream_t s) {
+hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan,
+                             const void *dx_dfv, float *grad_accum, int32_t M, int32_t *ready_ids,
+                             float *ready_grads, const int32_t *status, hipStream_t s) {
   if (img.n <= 0) return hipSuccess;
   const int D = cfg.dfv_dim;
-  int threads = ((D / 4 + 63) / 64) * 64;
+  const int cols = cfg.mlp_dtype == GEAR_BF16 ? 8 : 4;
+  int threads = ((D / cols + 63) / 64) * 64;
   if (threads > 256) threads = 256;
-  int blocks = img.n < 16384 ? img.n : 16384;
-  hipLaunchKernelGGL(k_accumulate, dim3(blocks), dim3(threads), 0, s, plan, dx, F, 2 * cfg.emb_dim, D, grad_accum, M,
-                     ready_ids, ready_grads, status);
+  int blocks = img.n < 32768 ? img.n : 32768;
+  if (cfg.mlp_dtype == GEAR_BF16)
+    hipLaunchKernelGGL(k_accumulate<bf16_t>, dim3(blocks), dim3(threads), 0, s, plan, (const bf16_t *)dx_dfv, D,
+                       grad_accum, M, ready_ids, ready_grads, status);
+  else
+    hipLaunchKernelGGL(k_accumulate<float>, dim3(blocks), dim3(threads), 0, s, plan, (const float *)dx_dfv, D,
+                       grad_accum, M, ready_ids, ready_grads, status);
   return hipGetLastError();
 }
 

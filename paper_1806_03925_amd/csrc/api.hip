@@ -140,7 +140,8 @@ bool make_layout(const gear_config &c, Layout *lay) {
   lay->logits = take(&cur, B * sizeof(float));
   lay->dz = take(&cur, B * sizeof(float));
   lay->loss_partial = take(&cur, logit_partial_floats(lay->in_dim[L - 1]) * sizeof(float));
-  lay->dx = take(&cur, B * F * sizeof(float));
+  lay->dx_emb = take(&cur, B * 2 * c.emb_dim * sizeof(float));
+  lay->dx_dfv = take(&cur, B * c.dfv_dim * ab);
   lay->wgrad_partial = take(&cur, max_partial);
   lay->colsum_partial = take(&cur, (size_t)lay->colsum_chunks * max_h * sizeof(float));
   lay->emb_partial = take(&cur, embedding_partial_floats(c) * sizeof(float));
@@ -240,9 +241,12 @@ gear_status gear_workspace_region(const gear_config *cfg, const char *name, size
   } else if (!strcmp(name, "logits")) {
     *offset = lay.logits;
     *bytes = B * sizeof(float);
-  } else if (!strcmp(name, "dx")) {
-    *offset = lay.dx;
-    *bytes = B * lay.F * sizeof(float);
+  } else if (!strcmp(name, "dx_emb")) {
+    *offset = lay.dx_emb;
+    *bytes = B * 2 * cfg->emb_dim * sizeof(float);
+  } else if (!strcmp(name, "dx_dfv")) {
+    *offset = lay.dx_dfv;
+    *bytes = B * cfg->dfv_dim * lay.act_bytes;
   } else {
     return GEAR_ERR_INVALID;
   }
@@ -357,7 +361,7 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   for (int l = 0; l < L - 1; ++l)
     GEAR_RUN(kFwd[l], launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l],
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
-                                     ws + lay.h[l], nullptr, status, s));
+                                     ws + lay.h[l], 0, nullptr, status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
   GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
   GEAR_RUN("logit_loss_sgd",
@@ -369,13 +373,14 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   // backward through the hidden layers down to dLoss/dx (all from the pre-step operand copies)
   // Each product that makes the delta of a hidden layer also leaves that layer's bias gradient (column
   // sums of the delta) as per-row-tile partials, which are added in tile order and applied at once.
-  float *dx = (float *)(ws + lay.dx);
+  float *dx_emb = (float *)(ws + lay.dx_emb);
+  void *dx_dfv = ws + lay.dx_dfv;
   float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
   for (int l = L - 2; l >= 0; --l) {
     if (l > 0) {
       const int parts = gemm_nt_colsum_parts(dt, B, lay.in_dim[l], lay.out_dim[l]);
       GEAR_RUN(kDgrad[l], launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l],
-                                         EPI_MASK, nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1],
+                                         EPI_MASK, nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1], 0,
                                          parts ? cpart : nullptr, status, s));
       if (parts)
         GEAR_RUN("bias_sgd", launch_partial_sgd(cpart, parts, lay.out_dim[l - 1], t->mlp_params + lay.b_off[l - 1], lr,
@@ -384,8 +389,9 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
         GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l - 1], B, lay.out_dim[l - 1], cpart,
                                                t->mlp_params + lay.b_off[l - 1], lr, status, s));
     } else {
-      GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_F32,
-                                         nullptr, nullptr, dx, nullptr, status, s));
+      // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type
+      GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_DX,
+                                         nullptr, dx_dfv, dx_emb, 2 * cfg->emb_dim, nullptr, status, s));
     }
   }
 
@@ -400,9 +406,9 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
 
   // SGD on the touched embedding rows, then the per-image gradient bookkeeping
   GEAR_RUN("embedding_update",
-           launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx, F, t->user_emb, t->url_emb,
+           launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
                                    (float *)(ws + lay.emb_partial), lr, status, s));
-  GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx, F, grad_accum, M, out->ready_ids,
+  GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
                                            out->ready_grads, status, s));
   GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
 
@@ -467,7 +473,7 @@ gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B,
     if (K % vec || N % vec || epilogue < EPI_BIAS_RELU || epilogue > EPI_F32) return GEAR_ERR_INVALID;
     if ((epilogue == EPI_BIAS_RELU && !bias) || (epilogue == EPI_MASK && (!aux || !aligned16(aux))))
       return GEAR_ERR_INVALID;
-    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, nullptr, status, s));
+    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, 0, nullptr, status, s));
   } else if (form == 1) {
     if (M % vec || N % vec || splits < 1 || splits > 64 || !partial) return GEAR_ERR_INVALID;
     GEAR_HIP(launch_gemm_tn_splitk(dtype, A, B, M, N, K, splits, partial, status, s));

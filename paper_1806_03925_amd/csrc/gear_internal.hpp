@@ -125,7 +125,7 @@ struct Layout {
   int32_t colsum_chunks;             // row chunks of the column-sum kernels
   size_t act_bytes;                  // sizeof(mlp_dtype)
 
-  size_t x, h[GEAR_MAX_LAYERS], delta[GEAR_MAX_LAYERS], logits, dz, loss_partial, dx;
+  size_t x, h[GEAR_MAX_LAYERS], delta[GEAR_MAX_LAYERS], logits, dz, loss_partial, dx_emb, dx_dfv;
   size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial, emb_partial;
   size_t occ_view;
   struct G {
@@ -167,11 +167,12 @@ enum GemmEpilogue {
   EPI_BIAS_RELU = 0,  // out(T)   = max(acc + bias[n], 0)
   EPI_MASK = 1,       // out(T)   = aux[m,n] > 0 ? acc : 0
   EPI_F32 = 2,        // out(f32) = acc
+  EPI_DX = 3,         // columns < split: out(f32)[M x split] = acc; others: aux(T)[M x (N - split)] = acc
 };
 // C[M x N] = A[M x K] * B[N x K]^T, both operands K-contiguous, type `dtype`.
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue,
-                          const float *bias, const void *aux, void *out, float *colpart, const int32_t *status,
-                          hipStream_t s);
+                          const float *bias, const void *aux, void *out, int split, float *colpart,
+                          const int32_t *status, hipStream_t s);
 int gemm_nt_colsum_parts(int dtype, int M, int N, int K);
 // dst[j] -= lr * sum_p partial[p][j], p ascending in a fixed two-level shape
 hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, float lr, const int32_t *status,
@@ -193,13 +194,13 @@ hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *pa
                              const int32_t *status, hipStream_t s);
 
 hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
-                                   const float *dx, int F, void *user_emb, void *url_emb, float *partials, float lr,
+                                   const float *dx_emb, void *user_emb, void *url_emb, float *partials, float lr,
                                    const int32_t *status, hipStream_t s);
 size_t embedding_partial_floats(const gear_config &cfg);
 
-hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan, const float *dx,
-                             int F, float *grad_accum, int32_t M, int32_t *ready_ids, float *ready_grads,
-                             const int32_t *status, hipStream_t s);
+hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, const AccumPlan &plan,
+                             const void *dx_dfv, float *grad_accum, int32_t M, int32_t *ready_ids,
+                             float *ready_grads, const int32_t *status, hipStream_t s);
 hipError_t launch_count_update(const GroupProblem &img, int32_t *counts, const int32_t *status, hipStream_t s);
 
 hipError_t launch_refresh(int dtype, void *dfv_cache, int64_t n_images, int dim, const int32_t *ids,

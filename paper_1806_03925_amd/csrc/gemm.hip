@@ -210,7 +210,7 @@ __device__ __forceinline__ void mma_tile(f32x16_v (&acc)[TM][TN], const T *As, c
 template <typename T, int EPI>
 __device__ __forceinline__ void epilogue_direct(const f32x16_v (&acc)[TM][TN], int m0, int n0, int wm, int wn,
                                                 int lane, int M, int N, const float *__restrict__ bias,
-                                                const T *__restrict__ aux, void *__restrict__ out) {
+                                                const T *__restrict__ aux, void *__restrict__ out, int split = 0) {
   const int c = lane & 31, g = lane >> 5;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -231,6 +231,12 @@ __device__ __forceinline__ void epilogue_direct(const f32x16_v (&acc)[TM][TN], i
           static_cast<T *>(out)[idx] = from_f32<T>(v > 0.0f ? v : 0.0f);
         } else if constexpr (EPI == EPI_MASK) {
           static_cast<T *>(out)[idx] = from_f32<T>(to_f32<T>(aux[idx]) > 0.0f ? v : 0.0f);
+        } else if constexpr (EPI == EPI_DX) {
+          // columns below `split` stay fp32 in `out`, the others go to `aux` in the operand type
+          if (n < split)
+            static_cast<float *>(out)[(size_t)m * split + n] = v;
+          else
+            const_cast<T *>(aux)[(size_t)m * (N - split) + (n - split)] = from_f32<T>(v);
         } else {
           static_cast<float *>(out)[idx] = v;
         }
@@ -374,31 +380,88 @@ __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_ad
   MFMA_BF16(acc[3][1], r3, s1);
 }
 
+// Results of the DMA kernel.  fp32 results are stored straight from the accumulator layout (a
+// half-wave covers 128 contiguous bytes).  bf16 results go through a per-wave LDS patch of 32 rows x
+// 64 columns so that every lane stores 16 contiguous bytes; the ReLU mask of a dgrad (EPI_MASK) is
+// read with the same 16-byte pattern, all of it before the first patch is written.  EPI_DX splits
+// the columns: below `split` fp32 into `out` [M x split], the rest bf16 into `aux` [M x (N - split)].
 template <int EPI>
 __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
                                                int wn, int lane, int M, int N, const float *__restrict__ bias,
-                                               const bf16_t *__restrict__ aux, void *__restrict__ out,
+                                               const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
                                                float (&colacc)[8]) {
   const int c = lane & 31, g = lane >> 5;
-  float bn[TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn * WN + j * 32 + c;
-    bn[j] = (EPI == EPI_BIAS_RELU && n < N) ? bias[n] : 0.0f;
+  const int wave_n0 = n0 + wn * WN;
+  // where this wave's columns go
+  bool direct_f32 = EPI == EPI_F32, mixed = false;
+  int ld_f32 = N, ld_bf = N, col_shift = 0;
+  bf16_t *out_bf = static_cast<bf16_t *>(out);
+  if constexpr (EPI == EPI_DX) {
+    ld_f32 = split;
+    ld_bf = N - split;
+    col_shift = split;
+    out_bf = const_cast<bf16_t *>(aux);
+    direct_f32 = wave_n0 + WN <= split;
+    mixed = !direct_f32 && wave_n0 < split;
   }
+  if (mixed) {  // the split falls inside this wave's columns: element by element
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    if constexpr (EPI == EPI_F32) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + c;
+        const int n = wave_n0 + j * 32 + c;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
-          if (m < M && n < N) static_cast<float *>(out)[(size_t)m * N + n] = acc[i][j][e];
+          if (m < M && n < N) {
+            if (n < split)
+              static_cast<float *>(out)[(size_t)m * ld_f32 + n] = acc[i][j][e];
+            else
+              out_bf[(size_t)m * ld_bf + (n - col_shift)] = f32_to_bf16(acc[i][j][e]);
+          }
         }
       }
-    } else {
+    return;
+  }
+  if (direct_f32) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = wave_n0 + j * 32 + c;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+          if (m < M && n < N) static_cast<float *>(out)[(size_t)m * ld_f32 + n] = acc[i][j][e];
+        }
+      }
+    return;
+  }
+  if constexpr (EPI != EPI_F32) {
+    float bn[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = wave_n0 + j * 32 + c;
+      bn[j] = (EPI == EPI_BIAS_RELU && n < N) ? bias[n] : 0.0f;
+    }
+    // lane's 16-byte pieces: rows it*8 + lane/8 of each 32-row tile, columns (lane%8)*8 .. +7
+    const int prow = lane >> 3, cv = (lane & 7) * 8;
+    const int n_vec = wave_n0 + cv;
+    Pack16 h[TM][4];
+    if constexpr (EPI == EPI_MASK) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int m = m0 + wm * WM + i * 32 + it * 8 + prow;
+          if (m < M && n_vec < N)
+            h[i][it].u = *reinterpret_cast<const uint4 *>(aux + (size_t)m * N + n_vec);
+          else
+            h[i][it].u = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -413,18 +476,16 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
-        const int row = it * 8 + (lane >> 3), cv = (lane & 7) * 8;
-        const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + cv;
+        const int row = it * 8 + prow;
+        const int m = m0 + wm * WM + i * 32 + row;
         Pack16 v;
         v.u = *reinterpret_cast<const uint4 *>(patch + row * WN + cv);
-        if (m < M && n < N) {
-          const size_t idx = (size_t)m * N + n;
+        if (m < M && n_vec < N) {
           if constexpr (EPI == EPI_MASK) {
-            Pack16 h;
-            h.u = *reinterpret_cast<const uint4 *>(aux + idx);
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-              const uint32_t lo = h.w[w] & 0xffffu, hi = h.w[w] >> 16;
+              // keep a half-word where the forward activation was positive (bf16 > 0: sign clear, not zero)
+              const uint32_t lo = h[i][it].w[w] & 0xffffu, hi = h[i][it].w[w] >> 16;
               uint32_t keep = 0u;
               if (lo != 0u && lo < 0x8000u) keep |= 0x0000ffffu;
               if (hi != 0u && hi < 0x8000u) keep |= 0xffff0000u;
@@ -434,7 +495,7 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
               colacc[2 * w + 1] += __uint_as_float(v.w[w] & 0xffff0000u);
             }
           }
-          *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(out) + idx) = v.u;
+          *reinterpret_cast<uint4 *>(out_bf + (size_t)m * ld_bf + (n_vec - col_shift)) = v.u;
         }
       }
       __builtin_amdgcn_wave_barrier();
@@ -448,7 +509,7 @@ constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
 template <int EPI>
 __global__ void __launch_bounds__(DTHREADS)
 k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K,
-              const float *__restrict__ bias, const bf16_t *__restrict__ aux, void *__restrict__ out,
+              const float *__restrict__ bias, const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
               float *__restrict__ colpart, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[STAGES * STAGE_ELEMS];   // [stage][A tile | B tile]
@@ -515,7 +576,7 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
   bf16_t *patch = lds + wave * 32 * WN;
   float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, colacc);
+  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, colacc);
   if constexpr (EPI == EPI_MASK) {
     if (colpart) {
       // colpart[m-tile][n] = sum over the tile's rows of the stored values: lanes that share lane % 8
@@ -702,7 +763,7 @@ constexpr size_t lds_bytes(size_t elem, int ldk) { return (size_t)(BM + BN) * ld
 template <typename T, int EPI>
 __global__ void __launch_bounds__(THREADS)
 k_gemm_nt(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K, const float *__restrict__ bias,
-          const T *__restrict__ aux, void *__restrict__ out, const int32_t *__restrict__ status) {
+          const T *__restrict__ aux, void *__restrict__ out, int split, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   constexpr int BK = Tile<T>::BK, LDK = Tile<T>::LDK;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -738,12 +799,12 @@ k_gemm_nt(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
     mma_tile<T>(acc, As, Bs, wm, wn, lane);
     __syncthreads();
   }
-  if constexpr (sizeof(T) == 2 && EPI != EPI_F32) {
+  if constexpr (sizeof(T) == 2 && EPI != EPI_F32 && EPI != EPI_DX) {
     bf16_t *patch = reinterpret_cast<bf16_t *>(smem) + wave * 64 * (WN + 8);
     epilogue_bf16<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, reinterpret_cast<const bf16_t *>(aux),
                        static_cast<bf16_t *>(out));
   } else {
-    epilogue_direct<T, EPI>(acc, m0, n0, wm, wn, lane, M, N, bias, aux, out);
+    epilogue_direct<T, EPI>(acc, m0, n0, wm, wn, lane, M, N, bias, aux, out, split);
   }
 }
 
@@ -808,18 +869,20 @@ __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ pa
 
 template <typename T>
 hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, const float *bias, const void *aux,
-                  void *out, float *colpart, const int32_t *status, hipStream_t s) {
+                  void *out, int split, float *colpart, const int32_t *status, hipStream_t s) {
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
   if constexpr (sizeof(T) == 2) {
     if (K % DK == 0) {
       const dim3 grid(((M + DM - 1) / DM) * ((N + DN - 1) / DN));
 #define GEAR_DMA(E)                                                                                               \
   hipLaunchKernelGGL((k_gemm_nt_dma<E>), grid, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, \
-                     bias, (const bf16_t *)aux, out, colpart, status)
+                     bias, (const bf16_t *)aux, out, split, colpart, status)
       if (epi == EPI_BIAS_RELU)
         GEAR_DMA(EPI_BIAS_RELU);
       else if (epi == EPI_MASK)
         GEAR_DMA(EPI_MASK);
+      else if (epi == EPI_DX)
+        GEAR_DMA(EPI_DX);
       else
         GEAR_DMA(EPI_F32);
 #undef GEAR_DMA
@@ -829,11 +892,13 @@ hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, co
   const size_t smem = lds_bytes(sizeof(T), Tile<T>::LDK);
 #define GEAR_NT(E)                                                                                                  \
   hipLaunchKernelGGL((k_gemm_nt<T, E>), grid, dim3(THREADS), smem, s, (const T *)A, (const T *)B, M, N, K, bias,    \
-                     (const T *)aux, out, status)
+                     (const T *)aux, out, split, status)
   if (epi == EPI_BIAS_RELU)
     GEAR_NT(EPI_BIAS_RELU);
   else if (epi == EPI_MASK)
     GEAR_NT(EPI_MASK);
+  else if (epi == EPI_DX)
+    GEAR_NT(EPI_DX);
   else
     GEAR_NT(EPI_F32);
 #undef GEAR_NT
@@ -861,11 +926,11 @@ int gemm_nt_colsum_parts(int dtype, int M, int N, int K) {
 }
 
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue_kind,
-                          const float *bias, const void *aux, void *out, float *colpart, const int32_t *status,
-                          hipStream_t s) {
+                          const float *bias, const void *aux, void *out, int split, float *colpart,
+                          const int32_t *status, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  return dtype == GEAR_BF16 ? run_nt<bf16_t>(A, B, M, N, K, epilogue_kind, bias, aux, out, colpart, status, s)
-                            : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, colpart, status, s);
+  return dtype == GEAR_BF16 ? run_nt<bf16_t>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, status, s)
+                            : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, status, s);
 }
 
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,

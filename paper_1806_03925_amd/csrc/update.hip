@@ -149,8 +149,9 @@ k_embedding_spans(Table users, Table urls, const int32_t *__restrict__ user_pos_
 }  // namespace
 
 hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
-                                   const float *dx, int F, void *user_emb, void *url_emb, float *partials, float lr,
+                                   const float *dx, void *user_emb, void *url_emb, float *partials, float lr,
                                    const int32_t *status, hipStream_t s) {
+  const int F = 2 * cfg.emb_dim;  // dx holds the two embedding slots of dLoss/dx only
   const int n = users.n > urls.n ? users.n : urls.n;
   if (n <= 0) return hipSuccess;
   const int d = cfg.emb_dim;
