@@ -176,12 +176,12 @@ bool make_layout(const gear_config &c, Layout *lay) {
 
 using namespace gear;
 
-// One helper stream and two events per device, created on first use and kept for the life of the
+// One helper stream and three events per device, created on first use and kept for the life of the
 // process: the integer grouping of a step runs beside its gather and forward pass.
 namespace {
 struct SideLane {
   hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, cast = nullptr;
   bool ready = false;
 };
 SideLane g_side[64];
@@ -194,6 +194,7 @@ SideLane *side_lane() {
     if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
     if (hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
     if (hipEventCreateWithFlags(&l.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&l.cast, hipEventDisableTiming) != hipSuccess) return nullptr;
     l.ready = true;
   }
   return &l;
@@ -333,31 +334,34 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   plan.row_view = (int32_t *)(ws + lay.row_view);
   plan.row_scale = (float *)(ws + lay.row_scale);
   plan.n_units = (int32_t *)(ws + lay.n_units);
-  // The grouping depends on the ids only: it runs on the helper stream while the main stream gathers
-  // and runs the forward pass, and is joined before the first kernel that changes caller state.
+  // What depends only on ids, counters and pre-step parameters runs on the helper stream while the main
+  // stream gathers and runs the forward pass: operand copies of the weights (needed by the first
+  // product), the grouping, the accumulation plan and the counter update.  The main stream waits for
+  // it before the first kernel that changes caller state, so the status word is final by then.
   SideLane *side = side_lane();
   if (!side) return GEAR_ERR_HIP;
   GEAR_HIP(hipEventRecord(side->fork, s));
   GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
   {
-    hipStream_t main_stream = s;
-    hipStream_t s = side->stream;  // the two launches below go to the helper stream
-    (void)main_stream;
+    hipStream_t s = side->stream;  // the launches of this block go to the helper stream
+    {
+      Span span_(prof, "cast_weights", s);
+      for (int l = 0; l < L; ++l)
+        GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt,
+                                     ws + lay.wc[l], ws + lay.wct[l], status, s));
+    }
+    GEAR_HIP(hipEventRecord(side->cast, s));
     GEAR_RUN("group_ids", launch_group(gb, status, s));
-    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap, out->n_ready,
-                                                   status, s));
+    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap,
+                                             out->n_ready, status, s));
+    GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
   }
   GEAR_HIP(hipEventRecord(side->join, side->stream));
 
   // forward
   void *x = ws + lay.x;
   GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
-  {
-    Span span_(prof, "cast_weights", s);
-    for (int l = 0; l < L; ++l)
-      GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt, ws + lay.wc[l],
-                                   ws + lay.wct[l], status, s));
-  }
+  GEAR_HIP(hipStreamWaitEvent(s, side->cast, 0));
   for (int l = 0; l < L - 1; ++l)
     GEAR_RUN(kFwd[l], launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l],
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
@@ -395,6 +399,17 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
     }
   }
 
+  // SGD on the touched embedding rows (helper stream, beside the weight-gradient products) and the
+  // per-image gradient bookkeeping; both only need dLoss/dx
+  GEAR_HIP(hipEventRecord(side->fork, s));
+  GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+  {
+    hipStream_t s = side->stream;
+    GEAR_RUN("embedding_update",
+             launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
+                                     (float *)(ws + lay.emb_partial), lr, status, s));
+  }
+  GEAR_HIP(hipEventRecord(side->join, side->stream));
   // SGD on the hidden layers' weights: split-K wgrad (logit layer and all biases are done above)
   for (int l = L - 2; l >= 0; --l) {
     const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
@@ -404,14 +419,8 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
                                              t->mlp_params + lay.w_off[l], lr, status, s));
   }
 
-  // SGD on the touched embedding rows, then the per-image gradient bookkeeping
-  GEAR_RUN("embedding_update",
-           launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
-                                   (float *)(ws + lay.emb_partial), lr, status, s));
   GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
                                            out->ready_grads, status, s));
-  GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
-
   if (out->dbg_img_unique && b->nnz > 0)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_unique, gb.p[2].unique, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_img_segoff)
@@ -420,6 +429,7 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_perm, gb.p[2].perm, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_n_img_unique)
     GEAR_HIP(hipMemcpyAsync(out->dbg_n_img_unique, gb.p[2].n_unique, 4, hipMemcpyDeviceToDevice, s));
+  GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
   return GEAR_OK;
 }
 
