@@ -273,10 +273,8 @@ class GearOracle:
                 # hidden deltas are MLP operands: ReLU mask, then operand rounding
                 delta = round_to(np.where(active[l], back, 0.0), self.prec.mlp)
             else:
-                # dLoss/dx is the delta of the input layer: its DFV slot is kept in the operand type
-                # like the other deltas, the two embedding slots stay unrounded
+                # dLoss/dx is never an operand of a contraction again: it stays unrounded
                 dx = back
-                dx[:, 2 * d:] = round_to(dx[:, 2 * d:], self.prec.mlp)
 
         # 4. Apply the Sparse Part's gradients (plain SGD on MLP and on the touched rows).
         self.mlp = [(round_to(W - lr * dW, self.prec.master), round_to(b - lr * db, self.prec.master))

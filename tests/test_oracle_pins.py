@@ -397,8 +397,8 @@ def test_bf16_mode_rounds_operands():
     o = small_oracle(rng, prec=Precision("bf16", "bf16", "bf16", "f32"))
     r = o.step(random_batch(rng, 5, 7, 5, 9), 0.1)
     assert np.array_equal(r.x, round_bf16(r.x))
-    assert np.array_equal(r.dx[:, 4:], round_bf16(r.dx[:, 4:]))             # DFV slot of dLoss/dx: a delta
-    assert not np.array_equal(r.dx[:, :4], round_bf16(r.dx[:, :4]))         # embedding slots: not rounded
+    assert not np.array_equal(r.dx[:, 4:], round_bf16(r.dx[:, 4:]))         # dLoss/dx is no operand: not rounded
+    assert not np.array_equal(r.dx[:, :4], round_bf16(r.dx[:, :4]))
     assert np.array_equal(o.user_emb._dense, round_bf16(o.user_emb._dense))
     assert all(np.array_equal(W, round_to(W, "f32")) for W, _ in o.mlp)
 
