@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--cpu-sample-views", type=int, default=65536,
                     help="views of the oracle's timed sample (0 = skip the CPU baseline)")
+    ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: write profiles/traffic.json from two rocprofv3 --pmc counter CSVs of this benchmark")
     return ap.parse_args()
 
 
@@ -74,23 +76,77 @@ class WorkModel:
         return work
 
 
-def source_hash():
+CSRC = os.path.join(ROOT, "paper_1806_03925_amd", "csrc")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+# span -> (substring of the kernel's name, launches of that kernel in one step, index among them in
+# launch order, source files whose change invalidates the recorded figure)
+TRAFFIC_KERNELS = {
+    "gather_pool": ("k_gather_pool", 1, 0, ["gather.hip"]),
+    "accumulate": ("k_accumulate", 1, 0, ["accum.hip"]),
+    "fwd_gemm_l0": ("k_gemm_nt_dma<0>", 2, 0, ["gemm.hip"]),
+    "fwd_gemm_l1": ("k_gemm_nt_dma<0>", 2, 1, ["gemm.hip"]),
+    "dgrad_gemm_l1": ("k_gemm_nt_dma<1>", 1, 0, ["gemm.hip"]),
+    "dgrad_gemm_l0": ("k_gemm_nt_dma<3>", 1, 0, ["gemm.hip"]),
+    "wgrad_gemm_l1": ("k_gemm_tn_dma", 2, 0, ["gemm.hip"]),
+    "wgrad_gemm_l0": ("k_gemm_tn_dma", 2, 1, ["gemm.hip"]),
+}
+
+
+def source_hash(files):
     h = hashlib.sha256()
-    csrc = os.path.join(ROOT, "paper_1806_03925_amd", "csrc")
-    for f in sorted(os.listdir(csrc)):
-        h.update(open(os.path.join(csrc, f), "rb").read())
+    for f in sorted(set(files) | {"gear_internal.hpp"}):
+        h.update(open(os.path.join(CSRC, f), "rb").read())
     return h.hexdigest()[:16]
 
 
-def recorded_traffic(kernel):
-    """HBM bytes per launch from the rocprofv3 counter runs, if they were taken on this source."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
-    if not os.path.exists(path):
+def recorded_traffic(span):
+    """HBM bytes per launch from the rocprofv3 counter runs, if the kernel's source is unchanged since."""
+    if not os.path.exists(TRAFFIC_FILE) or span not in TRAFFIC_KERNELS:
         return None
-    rec = json.load(open(path))
-    if rec.get("source_hash") != source_hash():
+    rec = json.load(open(TRAFFIC_FILE)).get("kernels", {}).get(span)
+    if rec is None or rec.get("source_hash") != source_hash(TRAFFIC_KERNELS[span][3]):
         return None
-    return rec.get("kernels", {}).get(kernel)
+    return rec["bytes"]
+
+
+def record_traffic(fetch_csv, write_csv, refresh_bytes):
+    """Turn two `rocprofv3 --pmc` runs of this benchmark (FETCH_SIZE, then WRITE_SIZE; counter CSVs) into
+    profiles/traffic.json.  Each counter is scaled by what it reads for the full DFV refresh, a plain
+    copy of `refresh_bytes` in and out."""
+    import csv
+
+    def per_kernel(path, counter):
+        rows = [r for r in csv.DictReader(open(path)) if r["Counter_Name"] == counter]
+        rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+        by_name = {}
+        for r in rows:
+            by_name.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+        return by_name
+
+    def pick(by_name, sub):
+        hits = [v for k, v in by_name.items() if sub in k]
+        assert len(hits) == 1, (sub, [k for k in by_name if sub in k])
+        return hits[0]
+
+    out = {"unit": "bytes per launch", "calibration": {}, "kernels": {}}
+    tables = {}
+    for key, path, counter in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+        tables[key] = per_kernel(path, counter)
+        copy = pick(tables[key], "k_refresh")
+        assert len(copy) == 1
+        out["calibration"][key + "_bytes_per_count"] = refresh_bytes / copy[0]
+    for span, (sub, per_step, index, files) in TRAFFIC_KERNELS.items():
+        rec = {"source_hash": source_hash(files)}
+        for key in ("fetch", "write"):
+            vals = pick(tables[key], sub)
+            assert len(vals) % per_step == 0, (span, len(vals))
+            mine = vals[index::per_step]
+            rec[key + "_bytes"] = float(np.mean(mine)) * out["calibration"][key + "_bytes_per_count"]
+            rec["launches"] = len(mine)
+        rec["bytes"] = rec["fetch_bytes"] + rec["write_bytes"]
+        out["kernels"][span] = rec
+    json.dump(out, open(TRAFFIC_FILE, "w"), indent=1, sort_keys=True)
+    print(json.dumps(out, indent=1, sort_keys=True))
 
 
 def cpu_baseline(wl, views):
@@ -120,12 +176,17 @@ def main():
               "the step has no multi-GPU path", file=sys.stderr)
         sys.exit(2)
 
-    import torch
-
-    import paper_1806_03925_amd as g
     from gear_inputs import PageViewSource, get_workload
 
     wl = get_workload(args.workload)
+    if args.record_traffic:
+        record_traffic(*args.record_traffic, refresh_bytes=wl.n_images * wl.dfv_dim * BYTES[wl.dfv_dtype])
+        return
+
+    import torch
+
+    import paper_1806_03925_amd as g
+
     torch.cuda.set_device(0)
     cfg = g.config_for(wl)
     st = g.GearState(cfg)
@@ -204,6 +265,7 @@ def main():
                 row.update(bound="hbm", achieved=amount / (avg_ms * 1e-3) / 1e9, unit="GB/s", peak=HBM_PEAK_GBS)
             row["frac"] = row["achieved"] / row["peak"]
             row["algorithmic_per_launch"] = amount
+            row["traffic"] = recorded_traffic(name)
         kernels.append(row)
     kernels.sort(key=lambda r: -r["ms_per_step"])
     dominant = next(r for r in kernels if "bound" in r)
