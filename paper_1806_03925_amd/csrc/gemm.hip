@@ -343,6 +343,10 @@ typedef uint32_t u32x4_v __attribute__((ext_vector_type(4)));
 #define LDS_READ16(dst, addr, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(dst) : "v"(addr) : "memory")
 #define MFMA_BF16(acc_, a_, b_) \
   acc_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_v, a_), __builtin_bit_cast(bf16x8_v, b_), acc_, 0, 0, 0)
+// The NT kernel takes the product as (B rows) x (A rows)^T: a lane then holds, for ONE row
+// m = lane % 32 of the result, the columns n = 8 (e / 4) + 4 (lane / 32) + e % 4 -- four consecutive
+// columns per group of four accumulator elements, which is what its epilogue packs and stores.
+#define MFMA_BF16_T(acc_, a_, b_) MFMA_BF16(acc_, b_, a_)
 
 __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_addr0, uint32_t a_addr1, uint32_t b_addr0,
                                           uint32_t b_addr1) {
@@ -361,37 +365,48 @@ __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_ad
   LDS_READ16(s0, b_addr1, 0);
   LDS_READ16(s1, b_addr1, 2048);
   asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3), "+v"(q0), "+v"(q1)::"memory");
-  MFMA_BF16(acc[0][0], p0, q0);
-  MFMA_BF16(acc[0][1], p0, q1);
-  MFMA_BF16(acc[1][0], p1, q0);
-  MFMA_BF16(acc[1][1], p1, q1);
-  MFMA_BF16(acc[2][0], p2, q0);
-  MFMA_BF16(acc[2][1], p2, q1);
-  MFMA_BF16(acc[3][0], p3, q0);
-  MFMA_BF16(acc[3][1], p3, q1);
+  MFMA_BF16_T(acc[0][0], p0, q0);
+  MFMA_BF16_T(acc[0][1], p0, q1);
+  MFMA_BF16_T(acc[1][0], p1, q0);
+  MFMA_BF16_T(acc[1][1], p1, q1);
+  MFMA_BF16_T(acc[2][0], p2, q0);
+  MFMA_BF16_T(acc[2][1], p2, q1);
+  MFMA_BF16_T(acc[3][0], p3, q0);
+  MFMA_BF16_T(acc[3][1], p3, q1);
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3), "+v"(s0), "+v"(s1)::"memory");
-  MFMA_BF16(acc[0][0], r0, s0);
-  MFMA_BF16(acc[0][1], r0, s1);
-  MFMA_BF16(acc[1][0], r1, s0);
-  MFMA_BF16(acc[1][1], r1, s1);
-  MFMA_BF16(acc[2][0], r2, s0);
-  MFMA_BF16(acc[2][1], r2, s1);
-  MFMA_BF16(acc[3][0], r3, s0);
-  MFMA_BF16(acc[3][1], r3, s1);
+  MFMA_BF16_T(acc[0][0], r0, s0);
+  MFMA_BF16_T(acc[0][1], r0, s1);
+  MFMA_BF16_T(acc[1][0], r1, s0);
+  MFMA_BF16_T(acc[1][1], r1, s1);
+  MFMA_BF16_T(acc[2][0], r2, s0);
+  MFMA_BF16_T(acc[2][1], r2, s1);
+  MFMA_BF16_T(acc[3][0], r3, s0);
+  MFMA_BF16_T(acc[3][1], r3, s1);
 }
 
-// Results of the DMA kernel.  fp32 results are stored straight from the accumulator layout (a
-// half-wave covers 128 contiguous bytes).  bf16 results go through a per-wave LDS patch of 32 rows x
-// 64 columns so that every lane stores 16 contiguous bytes; the ReLU mask of a dgrad (EPI_MASK) is
-// read with the same 16-byte pattern, all of it before the first patch is written.  EPI_DX splits
-// the columns: below `split` fp32 into `out` [M x split], the rest bf16 into `aux` [M x (N - split)].
+// Results of the DMA kernel.  A lane holds row m = lane % 32 of each 32 x 32 tile and, per group of
+// four accumulator elements, four consecutive columns.  fp32 results are stored from there as
+// 16-byte pieces.  bf16 results are converted in pairs (v_cvt_pk_bf16_f32), written as 8-byte pieces
+// into a per-wave LDS patch of 32 rows x 64 columns and read back row-wise so that every lane stores
+// 16 contiguous bytes and a row of the patch leaves as one 128-byte line; the ReLU mask of a dgrad
+// (EPI_MASK) is read with the same 16-byte pattern before the patch is written.  EPI_DX splits the
+// columns: below `split` fp32 into `out` [M x split], the rest bf16 into `aux` [M x (N - split)].
+typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+typedef float f32x2_v __attribute__((ext_vector_type(2)));
+constexpr int PATCH_LD = WN + 8;  // bf16 elements per patch row (144 bytes: the 8-byte writes of a wave spread over all banks)
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2_v v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_v));
+}
+
 template <int EPI>
 __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
                                                int wn, int lane, int M, int N, const float *__restrict__ bias,
                                                const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
                                                float (&colacc)[8]) {
   const int c = lane & 31, g = lane >> 5;
-  const int wave_n0 = n0 + wn * WN;
+  const int wave_m0 = m0 + wm * WM, wave_n0 = n0 + wn * WN;
   // where this wave's columns go
   bool direct_f32 = EPI == EPI_F32, mixed = false;
   int ld_f32 = N, ld_bf = N, col_shift = 0;
@@ -406,13 +421,13 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
   }
   if (mixed) {  // the split falls inside this wave's columns: element by element
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      const int m = wave_m0 + i * 32 + c;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = wave_n0 + j * 32 + c;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+          const int n = wave_n0 + j * 32 + 8 * (e / 4) + 4 * g + (e % 4);
           if (m < M && n < N) {
             if (n < split)
               static_cast<float *>(out)[(size_t)m * ld_f32 + n] = acc[i][j][e];
@@ -420,31 +435,38 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
               out_bf[(size_t)m * ld_bf + (n - col_shift)] = f32_to_bf16(acc[i][j][e]);
           }
         }
-      }
+    }
     return;
   }
   if (direct_f32) {
+    // column counts are multiples of 8, so a group of four columns is inside the matrix or outside
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      const int m = wave_m0 + i * 32 + c;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = wave_n0 + j * 32 + c;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
-          if (m < M && n < N) static_cast<float *>(out)[(size_t)m * ld_f32 + n] = acc[i][j][e];
+        for (int q = 0; q < 4; ++q) {
+          const int n = wave_n0 + j * 32 + 8 * q + 4 * g;
+          if (m < M && n < N)
+            *reinterpret_cast<float4 *>(static_cast<float *>(out) + (size_t)m * ld_f32 + n) =
+                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         }
-      }
+    }
     return;
   }
   if constexpr (EPI != EPI_F32) {
-    float bn[TN];
+    float bn[TN][16];
+    if constexpr (EPI == EPI_BIAS_RELU) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = wave_n0 + j * 32 + c;
-      bn[j] = (EPI == EPI_BIAS_RELU && n < N) ? bias[n] : 0.0f;
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int n = wave_n0 + j * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+          bn[j][e] = n < N ? bias[n] : 0.0f;
+        }
     }
-    // lane's 16-byte pieces: rows it*8 + lane/8 of each 32-row tile, columns (lane%8)*8 .. +7
+    // lane's 16-byte pieces: rows it*8 + lane/8 of each 32-row band, columns (lane%8)*8 .. +7
     const int prow = lane >> 3, cv = (lane & 7) * 8;
     const int n_vec = wave_n0 + cv;
     Pack16 h[TM][4];
@@ -453,7 +475,7 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-          const int m = m0 + wm * WM + i * 32 + it * 8 + prow;
+          const int m = wave_m0 + i * 32 + it * 8 + prow;
           if (m < M && n_vec < N)
             h[i][it].u = *reinterpret_cast<const uint4 *>(aux + (size_t)m * N + n_vec);
           else
@@ -465,21 +487,26 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float v = acc[i][j][e];
-          if constexpr (EPI == EPI_BIAS_RELU) {
-            v += bn[j];
-            v = v > 0.0f ? v : 0.0f;
+        for (int q = 0; q < 4; ++q) {
+          float v[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            v[r] = acc[i][j][4 * q + r];
+            if constexpr (EPI == EPI_BIAS_RELU) {
+              v[r] += bn[j][4 * q + r];
+              v[r] = v[r] > 0.0f ? v[r] : 0.0f;
+            }
           }
-          patch[(8 * (e / 4) + 4 * g + (e % 4)) * WN + j * 32 + c] = f32_to_bf16(v);
+          *reinterpret_cast<uint2 *>(patch + c * PATCH_LD + j * 32 + 8 * q + 4 * g) =
+              make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
         }
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
         const int row = it * 8 + prow;
-        const int m = m0 + wm * WM + i * 32 + row;
+        const int m = wave_m0 + i * 32 + row;
         Pack16 v;
-        v.u = *reinterpret_cast<const uint4 *>(patch + row * WN + cv);
+        v.u = *reinterpret_cast<const uint4 *>(patch + row * PATCH_LD + cv);
         if (m < M && n_vec < N) {
           if constexpr (EPI == EPI_MASK) {
 #pragma unroll
@@ -574,14 +601,14 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
   }
   wait_vm<0>();
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
-  bf16_t *patch = lds + wave * 32 * WN;
+  bf16_t *patch = lds + wave * 32 * PATCH_LD;
   float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, colacc);
   if constexpr (EPI == EPI_MASK) {
     if (colpart) {
       // colpart[m-tile][n] = sum over the tile's rows of the stored values: lanes that share lane % 8
       // hold the same eight columns, then the two waves that share the columns are added
-      float *s_col = reinterpret_cast<float *>(lds + 8 * 32 * WN);  // behind the eight output patches
+      float *s_col = reinterpret_cast<float *>(lds + 8 * 32 * PATCH_LD);  // behind the eight output patches
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float v = colacc[e];
