@@ -391,14 +391,7 @@ __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_ad
 // 16 contiguous bytes and a row of the patch leaves as one 128-byte line; the ReLU mask of a dgrad
 // (EPI_MASK) is read with the same 16-byte pattern before the patch is written.  EPI_DX splits the
 // columns: below `split` fp32 into `out` [M x split], the rest bf16 into `aux` [M x (N - split)].
-typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
-typedef float f32x2_v __attribute__((ext_vector_type(2)));
 constexpr int PATCH_LD = WN + 8;  // bf16 elements per patch row (144 bytes: the 8-byte writes of a wave spread over all banks)
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  const f32x2_v v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_v));
-}
 
 template <int EPI>
 __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,

@@ -47,7 +47,53 @@ constexpr int kMaxVecPerLane = 4;  // a lane owns up to 4 16-byte pieces of a ro
 //   delta[b, j] = dz * w[j] * [h[b, j] > 0]                      (delta of the last hidden layer)
 //   part_w[block][j] = sum_b dz_b h[b, j],  part_b[block] = sum_b dz_b,  part_loss[block] = sum_b loss_b
 //   part_d[block][j] = sum_b delta[b, j]                         (bias gradient of the last hidden layer)
-template <typename T>
+// G lanes (32 or 64) share a view and own NV 16-byte pieces of its row each; a wavefront takes
+// kLogitRows * (64 / G) views per round, all their rows in flight together.  The scalar part (loss,
+// sigmoid, dLoss/dz) of view u of a group is evaluated by the group's lane u, all views of the round
+// at once, and handed back to the group by a lane read.
+constexpr int kLogitRows = 4;
+
+template <int G> __device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int off = G / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// d = [h > 0] * dz * w for one 16-byte piece; returns the piece as stored and adds what was stored to gd
+template <typename T> struct DeltaPiece;
+template <> struct DeltaPiece<float> {
+  static __device__ __forceinline__ float4 make(const Vec16<float> &h, const Vec16<float> &w, float dz, float (&gw)[4],
+                                                 float (&gd)[4]) {
+    float d[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float hval = h.get(e);
+      gw[e] += dz * hval;
+      d[e] = hval > 0.0f ? dz * w.get(e) : 0.0f;
+      gd[e] += d[e];
+    }
+    return make_float4(d[0], d[1], d[2], d[3]);
+  }
+};
+template <> struct DeltaPiece<bf16_t> {
+  static __device__ __forceinline__ uint4 make(const Vec16<bf16_t> &h, const Vec16<bf16_t> &w, float dz, float (&gw)[8],
+                                                float (&gd)[8]) {
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const float h0 = h.get(e), h1 = h.get(e + 1);
+      gw[e] += dz * h0;
+      gw[e + 1] += dz * h1;
+      const uint32_t word = pack_bf16(h0 > 0.0f ? dz * w.get(e) : 0.0f, h1 > 0.0f ? dz * w.get(e + 1) : 0.0f);
+      gd[e] += __uint_as_float(word << 16);  // the stored (rounded) values
+      gd[e + 1] += __uint_as_float(word & 0xffff0000u);
+      o[e >> 1] = word;
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+  }
+};
+
+template <typename T, int NV, int G>
 __global__ void __launch_bounds__(256)
 k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__restrict__ bias,
              const float *__restrict__ label, int B, int H, int rows_per_block, float *__restrict__ logits,
@@ -56,83 +102,109 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
              const int32_t *__restrict__ status) {
   if (*status != 0) return;
   constexpr int VEC = Vec16<T>::N;
+  constexpr int GROUPS = kWave / G;            // views a wavefront handles side by side
+  constexpr int PARTS = 4 * GROUPS;            // partial sums per column in a workgroup
   __shared__ float s_red[4][2];
-  extern __shared__ float s_w[];  // [4][H] per-wave weight-gradient sums, then [4][H] delta sums
+  extern __shared__ float s_w[];  // [PARTS][H] weight-gradient sums, then [PARTS][H] delta sums
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int gl = lane & (G - 1), gi = lane / G;
   const int n_vec = H / VEC;
   const float b0 = bias[0], invB = 1.0f / (float)B;
 
-  Vec16<T> wv[kMaxVecPerLane];
-  float gw[kMaxVecPerLane][VEC], gd[kMaxVecPerLane][VEC];
+  Vec16<T> wv[NV];
+  float gw[NV][VEC], gd[NV][VEC];
 #pragma unroll
-  for (int i = 0; i < kMaxVecPerLane; ++i) {
-    const int v = lane + i * kWave;
+  for (int i = 0; i < NV; ++i) {
+    const int v = gl + i * G;
+    wv[i].v = decltype(wv[i].v){};
     if (v < n_vec) wv[i].v = *reinterpret_cast<const decltype(wv[i].v) *>(w + v * VEC);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) gw[i][e] = gd[i][e] = 0.0f;
   }
-  float loss_acc = 0.0f, dz_acc = 0.0f;
+  float loss_acc = 0.0f, dz_acc = 0.0f;  // partial sums of the views this lane evaluates
   const int r0 = blockIdx.x * rows_per_block, r1 = min(B, r0 + rows_per_block);
-  for (int view = r0 + wave; view < r1; view += 4) {
-    const T *hr = h + (size_t)view * H;
-    Vec16<T> hv[kMaxVecPerLane];
-    float dot = 0.0f;
+  constexpr int ROUND = kLogitRows * GROUPS;  // views per wavefront and round
+  for (int base = r0 + wave * ROUND; base < r1; base += 4 * ROUND) {
+    Vec16<T> hv[kLogitRows][NV];
+    float dot[kLogitRows];
 #pragma unroll
-    for (int i = 0; i < kMaxVecPerLane; ++i) {
-      const int v = lane + i * kWave;
-      if (v < n_vec) {
-        hv[i].v = *reinterpret_cast<const decltype(hv[i].v) *>(hr + v * VEC);
+    for (int u = 0; u < kLogitRows; ++u) {
+      const int view = base + u * GROUPS + gi;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) dot += hv[i].get(e) * wv[i].get(e);
+      for (int i = 0; i < NV; ++i) {
+        const int v = gl + i * G;
+        hv[u][i].v = decltype(hv[u][i].v){};
+        if (view < r1 && v < n_vec) hv[u][i].v = *reinterpret_cast<const decltype(hv[u][i].v) *>(h + (size_t)view * H + v * VEC);
       }
     }
-    const float z = wave_sum(dot) + b0;
-    const float y = label[view];
+#pragma unroll
+    for (int u = 0; u < kLogitRows; ++u) {
+      float d = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) d += hv[u][i].get(e) * wv[i].get(e);
+      dot[u] = group_sum<G>(d);
+    }
+    // lane u of a group evaluates the group's view u
+    float z = dot[0];
+#pragma unroll
+    for (int u = 1; u < kLogitRows; ++u) z = gl == u ? dot[u] : z;
+    z += b0;
+    const int my_view = base + gl * GROUPS + gi;
+    const bool mine = gl < kLogitRows && my_view < r1;
+    const float y = mine ? label[my_view] : 0.0f;
     const float ex = expf(-fabsf(z));
     const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
-    const float dz = (sig - y) * invB;
-    loss_acc += fmaxf(z, 0.0f) - z * y + log1pf(ex);
-    dz_acc += dz;
-    if (lane == 0) {
-      logits[view] = z;
-      dz_out[view] = dz;
+    const float dzv = (sig - y) * invB;
+    if (mine) {
+      loss_acc += fmaxf(z, 0.0f) - z * y + log1pf(ex);
+      dz_acc += dzv;
+      logits[my_view] = z;
+      dz_out[my_view] = dzv;
     }
-    T *dr = delta + (size_t)view * H;
 #pragma unroll
-    for (int i = 0; i < kMaxVecPerLane; ++i) {
-      const int v = lane + i * kWave;
-      if (v < n_vec) {
-        Vec16<T> dv = hv[i];
+    for (int u = 0; u < kLogitRows; ++u) {
+      const int view = base + u * GROUPS + gi;
+      const float dz = __shfl(dzv, gi * G + u, kWave);
+      if (view < r1) {
+        T *dr = delta + (size_t)view * H;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const float hval = hv[i].get(e);
-          gw[i][e] += dz * hval;
-          dv.set(e, hval > 0.0f ? dz * wv[i].get(e) : 0.0f);
-          gd[i][e] += dv.get(e);  // the stored (rounded) value
+        for (int i = 0; i < NV; ++i) {
+          const int v = gl + i * G;
+          if (v < n_vec)
+            *reinterpret_cast<decltype(hv[u][i].v) *>(dr + v * VEC) = DeltaPiece<T>::make(hv[u][i], wv[i], dz, gw[i], gd[i]);
         }
-        *reinterpret_cast<decltype(dv.v) *>(dr + v * VEC) = dv.v;
       }
     }
   }
-  // combine the four waves in wave order
+  // combine the groups of the four waves in a fixed order
 #pragma unroll
-  for (int i = 0; i < kMaxVecPerLane; ++i) {
-    const int v = lane + i * kWave;
+  for (int i = 0; i < NV; ++i) {
+    const int v = gl + i * G;
     if (v < n_vec)
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        s_w[wave * H + v * VEC + e] = gw[i][e];
-        s_w[(4 + wave) * H + v * VEC + e] = gd[i][e];
+        s_w[(wave * GROUPS + gi) * H + v * VEC + e] = gw[i][e];
+        s_w[(PARTS + wave * GROUPS + gi) * H + v * VEC + e] = gd[i][e];
       }
   }
+  loss_acc = wave_sum(loss_acc);
+  dz_acc = wave_sum(dz_acc);
   if (lane == 0) {
     s_red[wave][0] = loss_acc;
     s_red[wave][1] = dz_acc;
   }
   __syncthreads();
   for (int j = threadIdx.x; j < H; j += blockDim.x) {
-    part_w[(size_t)blockIdx.x * H + j] = ((s_w[j] + s_w[H + j]) + s_w[2 * H + j]) + s_w[3 * H + j];
-    part_d[(size_t)blockIdx.x * H + j] = ((s_w[4 * H + j] + s_w[5 * H + j]) + s_w[6 * H + j]) + s_w[7 * H + j];
+    float tw = 0.0f, td = 0.0f;
+#pragma unroll
+    for (int q = 0; q < PARTS; ++q) {
+      tw += s_w[q * H + j];
+      td += s_w[(PARTS + q) * H + j];
+    }
+    part_w[(size_t)blockIdx.x * H + j] = tw;
+    part_d[(size_t)blockIdx.x * H + j] = td;
   }
   if (threadIdx.x == 0) {
     part_loss[blockIdx.x] = ((s_red[0][0] + s_red[1][0]) + s_red[2][0]) + s_red[3][0];
@@ -250,15 +322,28 @@ hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, floa
   const int rows_per_block = (B + blocks - 1) / blocks;
   float *part_w = partials, *part_d = part_w + (size_t)kLossBlocks * H, *part_b = part_d + (size_t)kLossBlocks * H,
         *part_loss = part_b + kLossBlocks;
-  const size_t smem = 8 * (size_t)H * sizeof(float);
-  if (dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_logit_loss<bf16_t>, dim3(blocks), dim3(256), smem, s, (const bf16_t *)h,
-                       (const bf16_t *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz, (bf16_t *)delta,
-                       part_w, part_d, part_b, part_loss, status);
-  else
-    hipLaunchKernelGGL(k_logit_loss<float>, dim3(blocks), dim3(256), smem, s, (const float *)h,
-                       (const float *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz, (float *)delta,
-                       part_w, part_d, part_b, part_loss, status);
+  // lanes per view and 16-byte pieces per lane, from the width of the last hidden layer
+  const int n_vec = H / (dtype == GEAR_BF16 ? 8 : 4);
+#define GEAR_LOGIT(T, NV, G)                                                                                        \
+  hipLaunchKernelGGL((k_logit_loss<T, NV, G>), dim3(blocks), dim3(256), 2 * 4 * (kWave / G) * (size_t)H * sizeof(float), \
+                     s, (const T *)h, (const T *)wc_last, bias_last, label, B, H, rows_per_block, logits, dz,       \
+                     (T *)delta, part_w, part_d, part_b, part_loss, status)
+#define GEAR_LOGIT_T(T)                 \
+  if (n_vec <= 32)                      \
+    GEAR_LOGIT(T, 1, 32);               \
+  else if (n_vec <= 64)                 \
+    GEAR_LOGIT(T, 1, 64);               \
+  else if (n_vec <= 128)                \
+    GEAR_LOGIT(T, 2, 64);               \
+  else                                  \
+    GEAR_LOGIT(T, 4, 64)
+  if (dtype == GEAR_BF16) {
+    GEAR_LOGIT_T(bf16_t);
+  } else {
+    GEAR_LOGIT_T(float);
+  }
+#undef GEAR_LOGIT_T
+#undef GEAR_LOGIT
   hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, s, part_loss, blocks, B, loss, status);
   hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, part_w, blocks, H, w_last, lr, status);
   hipLaunchKernelGGL(k_partial_sgd, dim3(1), dim3(256), 0, s, part_b, blocks, 1, bias_last, lr, status);
