@@ -212,6 +212,23 @@ def test_workload_steps_free_running(name, batch, steps, lr):
     assert sum(orc.counts.values()) > 0
 
 
+@pytest.mark.parametrize("dtype,hidden", [
+    ("f32", (64, 512)),      # last hidden width 512 fp32: 128 16-byte pieces per row, two per lane
+    ("f32", (32, 1024)),     # 1024 fp32: four pieces per lane (the widest the logit layer takes)
+    ("bf16", (64, 1024)),    # 1024 bf16: two pieces per lane
+    ("bf16", (64, 8)),       # a single piece: most lanes of a group idle
+])
+def test_wide_and_narrow_last_hidden_layer(dtype, hidden):
+    """The logit/loss kernel picks lanes per view and pieces per lane from the last hidden width."""
+    wl = get_workload("tiny").scaled(layers=(*hidden, 1), mlp_dtype=dtype, emb_dtype=dtype, dfv_dtype=dtype)
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    for step in range(2):
+        b = src.batch(step, batch=389)
+        check_step(wl, st, orc, b, 0.05, f"{dtype} hidden {hidden} step {step}")
+    check_state(wl, st, orc, f"{dtype} hidden {hidden}")
+
+
 def test_same_step_twice_is_bit_identical():
     wl = get_workload("hotkey").scaled(n_images=500)
     outs = []
