@@ -212,9 +212,9 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
   }
 }
 
-__global__ void __launch_bounds__(64) k_loss_final(const float *__restrict__ loss_partial, int n, int B,
-                                                   float *__restrict__ loss, const int32_t *__restrict__ status) {
-  if (*status != 0) return;
+// loss = (sum of the workgroups' partial sums) / B, by one wavefront, in a fixed shape
+__device__ __forceinline__ void loss_final(const float *__restrict__ loss_partial, int n, int B,
+                                           float *__restrict__ loss) {
   float part[kLossBlocks / kWave];
 #pragma unroll
   for (int k = 0; k < kLossBlocks / kWave; ++k) {
@@ -266,13 +266,11 @@ k_colsum_partial(const T *__restrict__ src, int B, int H, int rows_per_chunk, fl
 
 // dst[j] -= lr * sum_p partial[p][j].  Eight columns per workgroup and 32 row lanes, each adding
 // every 32nd partial in order (eight loads in flight); then the 32 lanes are added in order.
-__global__ void __launch_bounds__(256) k_partial_sgd(const float *__restrict__ partial, int P, int H,
-                                                     float *__restrict__ dst, float lr,
-                                                     const int32_t *__restrict__ status) {
-  if (*status != 0) return;
+__device__ __forceinline__ void partial_sgd(const float *__restrict__ partial, int P, int H, float *__restrict__ dst,
+                                            float lr, int block) {
   __shared__ float s[32][8];
   const int c = threadIdx.x & 7, g = threadIdx.x >> 3;
-  const int j = blockIdx.x * 8 + c;
+  const int j = block * 8 + c;
   float acc = 0.0f;
   if (j < H) {
     int p = g;
@@ -292,6 +290,33 @@ __global__ void __launch_bounds__(256) k_partial_sgd(const float *__restrict__ p
 #pragma unroll
     for (int k = 0; k < 32; ++k) t += s[k][c];
     dst[j] -= lr * t;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_partial_sgd(const float *__restrict__ partial, int P, int H,
+                                                     float *__restrict__ dst, float lr,
+                                                     const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  partial_sgd(partial, P, H, dst, lr, blockIdx.x);
+}
+
+// Everything that follows k_logit_loss in one launch; blockIdx.y picks the job: 0 the logit layer's
+// weights, 1 the last hidden layer's bias, 2 the logit bias, 3 the loss.
+__global__ void __launch_bounds__(256)
+k_logit_finish(const float *__restrict__ part_w, const float *__restrict__ part_d, const float *__restrict__ part_b,
+               const float *__restrict__ part_loss, int P, int H, int B, float *__restrict__ w_last,
+               float *__restrict__ bias_hidden, float *__restrict__ bias_last, float *__restrict__ loss, float lr,
+               const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  if (blockIdx.y == 0) {
+    partial_sgd(part_w, P, H, w_last, lr, blockIdx.x);
+  } else if (blockIdx.y == 1) {
+    partial_sgd(part_d, P, H, bias_hidden, lr, blockIdx.x);
+  } else if (blockIdx.x == 0) {
+    if (blockIdx.y == 2)
+      partial_sgd(part_b, P, 1, bias_last, lr, 0);
+    else if (threadIdx.x < kWave)
+      loss_final(part_loss, P, B, loss);
   }
 }
 
@@ -344,10 +369,8 @@ hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, floa
   }
 #undef GEAR_LOGIT_T
 #undef GEAR_LOGIT
-  hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, s, part_loss, blocks, B, loss, status);
-  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, part_w, blocks, H, w_last, lr, status);
-  hipLaunchKernelGGL(k_partial_sgd, dim3(1), dim3(256), 0, s, part_b, blocks, 1, bias_last, lr, status);
-  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, part_d, blocks, H, bias_hidden, lr, status);
+  hipLaunchKernelGGL(k_logit_finish, dim3((H + 7) / 8, 4), dim3(256), 0, s, part_w, part_d, part_b, part_loss, blocks,
+                     H, B, w_last, bias_hidden, bias_last, loss, lr, status);
   return hipGetLastError();
 }
 
