@@ -875,16 +875,30 @@ k_gemm_tn(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
                               partial + (size_t)blockIdx.z * M * N);
 }
 
-// W -= lr * sum_z partial[z], z ascending
+// W -= lr * sum_z partial[z], z ascending; a thread owns four consecutive elements (count is a
+// multiple of 4 because layer widths are multiples of 8) and keeps eight partials in flight
 __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ partial, int splits, int64_t count,
                                                     float *__restrict__ w, float lr,
                                                     const int32_t *__restrict__ status) {
   if (*status != 0) return;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= count) return;
-  float g = 0.0f;
-  for (int z = 0; z < splits; ++z) g += partial[(size_t)z * count + i];
-  w[i] -= lr * g;
+  float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+  int z = 0;
+  for (; z + 8 <= splits; z += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const float4 *>(partial + (size_t)(z + k) * count + i);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) g.x += v[k].x, g.y += v[k].y, g.z += v[k].z, g.w += v[k].w;
+  }
+  for (; z < splits; ++z) {
+    const float4 v = *reinterpret_cast<const float4 *>(partial + (size_t)z * count + i);
+    g.x += v.x, g.y += v.y, g.z += v.z, g.w += v.w;
+  }
+  float4 cur = *reinterpret_cast<float4 *>(w + i);
+  cur.x -= lr * g.x, cur.y -= lr * g.y, cur.z -= lr * g.z, cur.w -= lr * g.w;
+  *reinterpret_cast<float4 *>(w + i) = cur;
 }
 
 template <typename T>
@@ -980,8 +994,8 @@ hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M,
 hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, float lr,
                              const int32_t *status, hipStream_t s) {
   if (count <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_splitk_sgd, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partial, splits, count, w,
-                     lr, status);
+  hipLaunchKernelGGL(k_splitk_sgd, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, s, partial, splits, count,
+                     w, lr, status);
   return hipGetLastError();
 }
 
