@@ -129,6 +129,7 @@ bool make_layout(const gear_config &c, Layout *lay) {
     lay->wct[l] = take(&cur, wn * ab);
     if (l < L - 1) {
       lay->h[l] = take(&cur, B * lay->out_dim[l] * ab);
+      lay->relu_bits[l] = take(&cur, B * lay->out_dim[l] / 8);
       lay->delta[l] = take(&cur, B * lay->out_dim[l] * ab);
       lay->splitk[l] = gemm_splitk_for(lay->out_dim[l], lay->in_dim[l], c.max_batch);
       const size_t pb = (size_t)lay->splitk[l] * wn * sizeof(float);
@@ -362,10 +363,17 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   void *x = ws + lay.x;
   GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
   GEAR_HIP(hipStreamWaitEvent(s, side->cast, 0));
+  // A hidden layer below the last one also leaves the sign bitmap of its activations when both its
+  // own product and the dgrad product that masks with it run in the kernel that knows bitmaps: the
+  // backward pass then reads one bit per unit instead of the activation.
+  uint8_t *relu_bits[GEAR_MAX_LAYERS] = {};
+  for (int l = 0; l + 2 < L; ++l)
+    if (gemm_nt_has_bits(dt, lay.in_dim[l]) && gemm_nt_has_bits(dt, lay.out_dim[l + 1]))
+      relu_bits[l] = (uint8_t *)(ws + lay.relu_bits[l]);
   for (int l = 0; l < L - 1; ++l)
     GEAR_RUN(kFwd[l], launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l],
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
-                                     ws + lay.h[l], 0, nullptr, status, s));
+                                     ws + lay.h[l], 0, nullptr, relu_bits[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
   GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
   GEAR_RUN("logit_loss_sgd",
@@ -383,9 +391,11 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
   for (int l = L - 2; l >= 0; --l) {
     if (l > 0) {
       const int parts = gemm_nt_colsum_parts(dt, B, lay.in_dim[l], lay.out_dim[l]);
+      const bool by_bits = relu_bits[l - 1] != nullptr;
       GEAR_RUN(kDgrad[l], launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l],
-                                         EPI_MASK, nullptr, ws + lay.h[l - 1], ws + lay.delta[l - 1], 0,
-                                         parts ? cpart : nullptr, status, s));
+                                         by_bits ? EPI_MASK_BITS : EPI_MASK, nullptr,
+                                         by_bits ? (const void *)relu_bits[l - 1] : (const void *)(ws + lay.h[l - 1]),
+                                         ws + lay.delta[l - 1], 0, parts ? cpart : nullptr, nullptr, status, s));
       if (parts)
         GEAR_RUN("bias_sgd", launch_partial_sgd(cpart, parts, lay.out_dim[l - 1], t->mlp_params + lay.b_off[l - 1], lr,
                                                 status, s));
@@ -395,7 +405,7 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
     } else {
       // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type
       GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_DX,
-                                         nullptr, dx_dfv, dx_emb, 2 * cfg->emb_dim, nullptr, status, s));
+                                         nullptr, dx_dfv, dx_emb, 2 * cfg->emb_dim, nullptr, nullptr, status, s));
     }
   }
 
@@ -483,7 +493,7 @@ gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B,
     if (K % vec || N % vec || epilogue < EPI_BIAS_RELU || epilogue > EPI_F32) return GEAR_ERR_INVALID;
     if ((epilogue == EPI_BIAS_RELU && !bias) || (epilogue == EPI_MASK && (!aux || !aligned16(aux))))
       return GEAR_ERR_INVALID;
-    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, 0, nullptr, status, s));
+    GEAR_HIP(launch_gemm_nt(dtype, A, B, M, N, K, epilogue, bias, aux, out, 0, nullptr, nullptr, status, s));
   } else if (form == 1) {
     if (M % vec || N % vec || splits < 1 || splits > 64 || !partial) return GEAR_ERR_INVALID;
     GEAR_HIP(launch_gemm_tn_splitk(dtype, A, B, M, N, K, splits, partial, status, s));

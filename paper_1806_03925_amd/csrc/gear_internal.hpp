@@ -134,6 +134,7 @@ struct Layout {
   size_t act_bytes;                  // sizeof(mlp_dtype)
 
   size_t x, h[GEAR_MAX_LAYERS], delta[GEAR_MAX_LAYERS], logits, dz, loss_partial, dx_emb, dx_dfv;
+  size_t relu_bits[GEAR_MAX_LAYERS];  // [B x out/8] sign bitmaps of the hidden activations
   size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial, emb_partial;
   size_t occ_view;
   struct G {
@@ -176,12 +177,16 @@ enum GemmEpilogue {
   EPI_MASK = 1,       // out(T)   = aux[m,n] > 0 ? acc : 0
   EPI_F32 = 2,        // out(f32) = acc
   EPI_DX = 3,         // columns < split: out(f32)[M x split] = acc; others: aux(T)[M x (N - split)] = acc
+  EPI_MASK_BITS = 4,  // EPI_MASK with aux = the bitmap [M x N/8] an EPI_BIAS_RELU product left in `relu_bits`
 };
 // C[M x N] = A[M x K] * B[N x K]^T, both operands K-contiguous, type `dtype`.
+// relu_bits (EPI_BIAS_RELU only, may be NULL): bit (n % 8) of byte [m][n / 8] = (out[m][n] > 0); only
+// written by the kernel gemm_nt_has_bits() names, which is also the only one that takes EPI_MASK_BITS.
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue,
                           const float *bias, const void *aux, void *out, int split, float *colpart,
-                          const int32_t *status, hipStream_t s);
+                          uint8_t *relu_bits, const int32_t *status, hipStream_t s);
 int gemm_nt_colsum_parts(int dtype, int M, int N, int K);
+bool gemm_nt_has_bits(int dtype, int K);
 // dst[j] -= lr * sum_p partial[p][j], p ascending in a fixed two-level shape
 hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, float lr, const int32_t *status,
                               hipStream_t s);

@@ -397,7 +397,7 @@ template <int EPI>
 __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
                                                int wn, int lane, int M, int N, const float *__restrict__ bias,
                                                const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
-                                               float (&colacc)[8]) {
+                                               uint8_t *__restrict__ relu_bits, float (&colacc)[8]) {
   const int c = lane & 31, g = lane >> 5;
   const int wave_m0 = m0 + wm * WM, wave_n0 = n0 + wn * WN;
   // where this wave's columns go
@@ -462,7 +462,8 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
     // lane's 16-byte pieces: rows it*8 + lane/8 of each 32-row band, columns (lane%8)*8 .. +7
     const int prow = lane >> 3, cv = (lane & 7) * 8;
     const int n_vec = wave_n0 + cv;
-    Pack16 h[TM][4];
+    Pack16 h[EPI == EPI_MASK ? TM : 1][4];
+    uint32_t hbits[EPI == EPI_MASK_BITS ? TM : 1][4];  // eight sign bits per piece
     if constexpr (EPI == EPI_MASK) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -473,6 +474,16 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
             h[i][it].u = *reinterpret_cast<const uint4 *>(aux + (size_t)m * N + n_vec);
           else
             h[i][it].u = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+    if constexpr (EPI == EPI_MASK_BITS) {
+      const uint8_t *bits = reinterpret_cast<const uint8_t *>(aux);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int m = wave_m0 + i * 32 + it * 8 + prow;
+          hbits[i][it] = (m < M && n_vec < N) ? bits[(size_t)m * (N >> 3) + (n_vec >> 3)] : 0u;
         }
     }
 #pragma unroll
@@ -501,14 +512,31 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
         Pack16 v;
         v.u = *reinterpret_cast<const uint4 *>(patch + row * PATCH_LD + cv);
         if (m < M && n_vec < N) {
-          if constexpr (EPI == EPI_MASK) {
+          if constexpr (EPI == EPI_BIAS_RELU) {
+            if (relu_bits) {
+              // results are >= 0: a value is positive exactly when its bf16 pattern is not zero
+              uint32_t byte = 0u;
+#pragma unroll
+              for (int w = 0; w < 4; ++w) {
+                if (v.w[w] & 0x0000ffffu) byte |= 1u << (2 * w);
+                if (v.w[w] & 0xffff0000u) byte |= 2u << (2 * w);
+              }
+              relu_bits[(size_t)m * (N >> 3) + (n_vec >> 3)] = (uint8_t)byte;
+            }
+          }
+          if constexpr (EPI == EPI_MASK || EPI == EPI_MASK_BITS) {
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-              // keep a half-word where the forward activation was positive (bf16 > 0: sign clear, not zero)
-              const uint32_t lo = h[i][it].w[w] & 0xffffu, hi = h[i][it].w[w] >> 16;
               uint32_t keep = 0u;
-              if (lo != 0u && lo < 0x8000u) keep |= 0x0000ffffu;
-              if (hi != 0u && hi < 0x8000u) keep |= 0xffff0000u;
+              if constexpr (EPI == EPI_MASK) {
+                // keep a half-word where the forward activation was positive (bf16 > 0: sign clear, not zero)
+                const uint32_t lo = h[i][it].w[w] & 0xffffu, hi = h[i][it].w[w] >> 16;
+                if (lo != 0u && lo < 0x8000u) keep |= 0x0000ffffu;
+                if (hi != 0u && hi < 0x8000u) keep |= 0xffff0000u;
+              } else {
+                if (hbits[i][it] & (1u << (2 * w))) keep |= 0x0000ffffu;
+                if (hbits[i][it] & (2u << (2 * w))) keep |= 0xffff0000u;
+              }
               v.w[w] &= keep;
               // column sums of what is stored (the bias gradient of the layer below)
               colacc[2 * w] += __uint_as_float(v.w[w] << 16);
@@ -530,7 +558,7 @@ template <int EPI>
 __global__ void __launch_bounds__(DTHREADS)
 k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K,
               const float *__restrict__ bias, const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
-              float *__restrict__ colpart, const int32_t *__restrict__ status) {
+              float *__restrict__ colpart, uint8_t *__restrict__ relu_bits, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[STAGES * STAGE_ELEMS];   // [stage][A tile | B tile]
 
@@ -596,8 +624,8 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
   bf16_t *patch = lds + wave * 32 * PATCH_LD;
   float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, colacc);
-  if constexpr (EPI == EPI_MASK) {
+  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, relu_bits, colacc);
+  if constexpr (EPI == EPI_MASK || EPI == EPI_MASK_BITS) {
     if (colpart) {
       // colpart[m-tile][n] = sum over the tile's rows of the stored values: lanes that share lane % 8
       // hold the same eight columns, then the two waves that share the columns are added
@@ -903,18 +931,20 @@ __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ pa
 
 template <typename T>
 hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, const float *bias, const void *aux,
-                  void *out, int split, float *colpart, const int32_t *status, hipStream_t s) {
+                  void *out, int split, float *colpart, uint8_t *relu_bits, const int32_t *status, hipStream_t s) {
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
   if constexpr (sizeof(T) == 2) {
     if (K % DK == 0) {
       const dim3 grid(((M + DM - 1) / DM) * ((N + DN - 1) / DN));
 #define GEAR_DMA(E)                                                                                               \
   hipLaunchKernelGGL((k_gemm_nt_dma<E>), grid, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, \
-                     bias, (const bf16_t *)aux, out, split, colpart, status)
+                     bias, (const bf16_t *)aux, out, split, colpart, relu_bits, status)
       if (epi == EPI_BIAS_RELU)
         GEAR_DMA(EPI_BIAS_RELU);
       else if (epi == EPI_MASK)
         GEAR_DMA(EPI_MASK);
+      else if (epi == EPI_MASK_BITS)
+        GEAR_DMA(EPI_MASK_BITS);
       else if (epi == EPI_DX)
         GEAR_DMA(EPI_DX);
       else
@@ -959,12 +989,17 @@ int gemm_nt_colsum_parts(int dtype, int M, int N, int K) {
   return (dtype == GEAR_BF16 && K % DK == 0 && M > 0) ? (M + DM - 1) / DM : 0;
 }
 
+// The sign bitmap of a bias + ReLU product is written, and taken as a mask, by the DMA kernel only.
+bool gemm_nt_has_bits(int dtype, int K) { return dtype == GEAR_BF16 && K % DK == 0; }
+
 hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N, int K, int epilogue_kind,
                           const float *bias, const void *aux, void *out, int split, float *colpart,
-                          const int32_t *status, hipStream_t s) {
+                          uint8_t *relu_bits, const int32_t *status, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  return dtype == GEAR_BF16 ? run_nt<bf16_t>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, status, s)
-                            : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, status, s);
+  if (epilogue_kind == EPI_MASK_BITS && !gemm_nt_has_bits(dtype, K)) return hipErrorInvalidValue;
+  return dtype == GEAR_BF16
+             ? run_nt<bf16_t>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, relu_bits, status, s)
+             : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, relu_bits, status, s);
 }
 
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
