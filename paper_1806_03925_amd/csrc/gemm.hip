@@ -325,16 +325,21 @@ struct DmaPlan {
   size_t a_off[2], b_off[2];  // element offsets of this lane's 16-byte pieces at k0 = 0
 };
 
-__device__ __forceinline__ void dma_tile(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const DmaPlan &p,
-                                         int k0, bf16_t *As, bf16_t *Bs, int wave) {
+// Two consecutive k-tiles at once: a 128-byte line of an operand row holds the row's share of both,
+// and its two 64-byte halves are requested by back-to-back instructions of one wave, which meet in
+// the vector cache -- one L2 access per line instead of two.
+__device__ __forceinline__ void dma_pair(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const DmaPlan &p,
+                                         int k0, int k1, bf16_t *s0, bf16_t *s1, int wave) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-    __builtin_amdgcn_global_load_lds((const void *)(A + p.a_off[i] + k0), (lds_ptr_t)(As + (i * 8 + wave) * 512), 16, 0,
-                                     0);
+  for (int i = 0; i < 2; ++i) {
+    __builtin_amdgcn_global_load_lds((const void *)(A + p.a_off[i] + k0), (lds_ptr_t)(s0 + (i * 8 + wave) * 512), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const void *)(A + p.a_off[i] + k1), (lds_ptr_t)(s1 + (i * 8 + wave) * 512), 16, 0, 0);
+  }
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-    __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + k0), (lds_ptr_t)(Bs + (i * 8 + wave) * 512), 16, 0,
-                                     0);
+  for (int i = 0; i < 2; ++i) {
+    __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + k0), (lds_ptr_t)(s0 + A_ELEMS + (i * 8 + wave) * 512), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + k1), (lds_ptr_t)(s1 + A_ELEMS + (i * 8 + wave) * 512), 16, 0, 0);
+  }
 }
 
 // MFMA operands are fetched with explicit ds_read_b128 so that the only waits on the LDS path are
@@ -598,27 +603,22 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   const int nk = K / DK;
-#pragma unroll
-  for (int p = 0; p < STAGES - 1; ++p)
-    if (p < nk) dma_tile(A, B, plan, p * DK, lds + p * STAGE_ELEMS, lds + p * STAGE_ELEMS + A_ELEMS, wave);
-
-  // tile t is consumed from stage t % 4 while tiles t+1 and t+2 are in flight and t+3 is issued
-  int stage = 0;
+  // Tiles t and t + 1 (t even) are copied together into stages t % 4 and (t + 1) % 4 while the pair
+  // before them is multiplied: one wait and one barrier per pair.  When nk is odd the last pair's
+  // second half copies the last tile again, into a stage nobody reads.
+  auto issue = [&](int t) {
+    const int t1 = min(t + 1, nk - 1);
+    dma_pair(A, B, plan, t * DK, t1 * DK, lds + (t & 3) * STAGE_ELEMS, lds + ((t + 1) & 3) * STAGE_ELEMS, wave);
+  };
+  issue(0);
   for (int t = 0; t < nk; ++t) {
-    if (t + 2 < nk)
-      wait_vm<8>();
-    else if (t + 1 < nk)
-      wait_vm<4>();
-    else
-      wait_vm<0>();
-    block_barrier();
-    if (t + 3 < nk) {
-      const int ns = (stage + 3) & 3;
-      dma_tile(A, B, plan, (t + 3) * DK, lds + ns * STAGE_ELEMS, lds + ns * STAGE_ELEMS + A_ELEMS, wave);
+    if ((t & 1) == 0) {
+      wait_vm<0>();     // this wave's share of tiles t and t + 1 has landed
+      block_barrier();  // ... everybody's has, and everybody is done reading tiles t - 2 and t - 1
+      if (t + 2 < nk) issue(t + 2);
     }
-    const uint32_t so = (uint32_t)stage * (2u * STAGE_ELEMS);
+    const uint32_t so = (uint32_t)(t & 3) * (2u * STAGE_ELEMS);
     mma_stage(acc, a_rel[0] + so, a_rel[1] + so, b_rel[0] + so, b_rel[1] + so);
-    stage = (stage + 1) & 3;
   }
   wait_vm<0>();
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
