@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--cpu-sample-views", type=int, default=65536,
+    ap.add_argument("--cpu-sample-views", type=int, default=131072,
                     help="views of the oracle's timed sample (0 = skip the CPU baseline)")
     ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: write profiles/traffic.json from two rocprofv3 --pmc counter CSVs of this benchmark")
@@ -150,7 +150,7 @@ def record_traffic(fetch_csv, write_csv, refresh_bytes):
 
 
 def cpu_baseline(wl, views):
-    """The oracle as it stands, timed on this host over `views` page views of step 0's batch."""
+    """The oracle as it stands, timed on this host over one batch of `views` page views."""
     from threadpoolctl import threadpool_info
 
     from gear_inputs import PageViewSource
@@ -165,8 +165,8 @@ def cpu_baseline(wl, views):
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": views / dt, "unit": "page-views/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 oracle step over the first {views} views of the {wl.name} workload's batch 0 "
-                      f"({dt:.1f} s; table rows materialised beforehand)"}
+            "sample": f"1 oracle step over one batch of {views} views drawn the way the {wl.name} workload draws "
+                      f"its batches ({dt:.1f} s; table rows materialised beforehand)"}
 
 
 def main():
