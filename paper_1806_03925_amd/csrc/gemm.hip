@@ -559,6 +559,29 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
 constexpr int STAGES = 4;
 constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
 
+// Tiles t and t + 1 (t even) are copied together into stages t % 4 and (t + 1) % 4 while the pair
+// before them is multiplied: one wait and one barrier per pair.  When nk is odd the last pair's
+// second half copies the last tile again, into a stage nobody reads.
+template <bool MMA>
+__device__ __forceinline__ void nt_main_loop(f32x16_v (&acc)[TM][TN], const bf16_t *__restrict__ A,
+                                             const bf16_t *__restrict__ B, const DmaPlan &plan, bf16_t *lds, int nk,
+                                             int wave, const uint32_t (&a_rel)[2], const uint32_t (&b_rel)[2]) {
+  auto issue = [&](int t) {
+    const int t1 = min(t + 1, nk - 1);
+    dma_pair(A, B, plan, t * DK, t1 * DK, lds + (t & 3) * STAGE_ELEMS, lds + ((t + 1) & 3) * STAGE_ELEMS, wave);
+  };
+  issue(0);
+  for (int t = 0; t < nk; ++t) {
+    if ((t & 1) == 0) {
+      wait_vm<0>();     // this wave's share of tiles t and t + 1 has landed
+      block_barrier();  // ... everybody's has, and everybody is done reading tiles t - 2 and t - 1
+      if (t + 2 < nk) issue(t + 2);
+    }
+    const uint32_t so = (uint32_t)(t & 3) * (2u * STAGE_ELEMS);
+    if constexpr (MMA) mma_stage(acc, a_rel[0] + so, a_rel[1] + so, b_rel[0] + so, b_rel[1] + so);
+  }
+}
+
 template <int EPI>
 __global__ void __launch_bounds__(DTHREADS)
 k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K,
@@ -602,24 +625,12 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  const int nk = K / DK;
-  // Tiles t and t + 1 (t even) are copied together into stages t % 4 and (t + 1) % 4 while the pair
-  // before them is multiplied: one wait and one barrier per pair.  When nk is odd the last pair's
-  // second half copies the last tile again, into a stage nobody reads.
-  auto issue = [&](int t) {
-    const int t1 = min(t + 1, nk - 1);
-    dma_pair(A, B, plan, t * DK, t1 * DK, lds + (t & 3) * STAGE_ELEMS, lds + ((t + 1) & 3) * STAGE_ELEMS, wave);
-  };
-  issue(0);
-  for (int t = 0; t < nk; ++t) {
-    if ((t & 1) == 0) {
-      wait_vm<0>();     // this wave's share of tiles t and t + 1 has landed
-      block_barrier();  // ... everybody's has, and everybody is done reading tiles t - 2 and t - 1
-      if (t + 2 < nk) issue(t + 2);
-    }
-    const uint32_t so = (uint32_t)(t & 3) * (2u * STAGE_ELEMS);
-    mma_stage(acc, a_rel[0] + so, a_rel[1] + so, b_rel[0] + so, b_rel[1] + so);
-  }
+  // in a tile whose right part lies beyond N, the waves without columns copy tiles and meet the
+  // barriers but skip the operand reads and the products
+  if (n0 + wn * WN < N)
+    nt_main_loop<true>(acc, A, B, plan, lds, K / DK, wave, a_rel, b_rel);
+  else
+    nt_main_loop<false>(acc, A, B, plan, lds, K / DK, wave, a_rel, b_rel);
   wait_vm<0>();
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
   bf16_t *patch = lds + wave * 32 * PATCH_LD;
@@ -713,6 +724,31 @@ __device__ __forceinline__ void mma_stage_tn(f32x16_v (&acc)[TM][TN], uint32_t a
 #undef TN_KSTEP
 }
 
+template <bool MMA>
+__device__ __forceinline__ void tn_main_loop(f32x16_v (&acc)[TM][TN], const bf16_t *__restrict__ A,
+                                             const bf16_t *__restrict__ B, const TnPlan &plan, int k_begin, int nk, int M,
+                                             int N, unsigned char *lds, int wave, uint32_t a_even, uint32_t a_odd,
+                                             uint32_t b_even, uint32_t b_odd) {
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < nk) dma_tile_tn(A, B, plan, k_begin + p * DK, M, N, lds + p * TSTAGE, wave);
+
+  int stage = 0;
+  for (int t = 0; t < nk; ++t) {
+    if (t + 2 < nk)
+      wait_vm<8>();
+    else if (t + 1 < nk)
+      wait_vm<4>();
+    else
+      wait_vm<0>();
+    block_barrier();
+    if (t + 3 < nk) dma_tile_tn(A, B, plan, k_begin + (t + 3) * DK, M, N, lds + ((stage + 3) & 3) * TSTAGE, wave);
+    const uint32_t so = (uint32_t)stage * TSTAGE;
+    if constexpr (MMA) mma_stage_tn(acc, a_even + so, a_odd + so, b_even + so, b_odd + so);
+    stage = (stage + 1) & 3;
+  }
+}
+
 __global__ void __launch_bounds__(DTHREADS)
 k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K, int k_chunk,
               float *__restrict__ partial, const int32_t *__restrict__ status) {
@@ -771,24 +807,12 @@ k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   const int nk = (k_end - k_begin + DK - 1) / DK;   // k_end - k_begin is a multiple of DK (checked by the host)
-#pragma unroll
-  for (int p = 0; p < STAGES - 1; ++p)
-    if (p < nk) dma_tile_tn(A, B, plan, k_begin + p * DK, M, N, lds + p * TSTAGE, wave);
-
-  int stage = 0;
-  for (int t = 0; t < nk; ++t) {
-    if (t + 2 < nk)
-      wait_vm<8>();
-    else if (t + 1 < nk)
-      wait_vm<4>();
-    else
-      wait_vm<0>();
-    block_barrier();
-    if (t + 3 < nk) dma_tile_tn(A, B, plan, k_begin + (t + 3) * DK, M, N, lds + ((stage + 3) & 3) * TSTAGE, wave);
-    const uint32_t so = (uint32_t)stage * TSTAGE;
-    mma_stage_tn(acc, a_even + so, a_odd + so, b_even + so, b_odd + so);
-    stage = (stage + 1) & 3;
-  }
+  // in a tile whose right part lies beyond N, the waves without columns copy tiles and meet the
+  // barriers but skip the operand reads and the products
+  if (n0 + wn * WN < N)
+    tn_main_loop<true>(acc, A, B, plan, k_begin, nk, M, N, lds, wave, a_even, a_odd, b_even, b_odd);
+  else
+    tn_main_loop<false>(acc, A, B, plan, k_begin, nk, M, N, lds, wave, a_even, a_odd, b_even, b_odd);
   // fp32 partial of this k range
   float *dst = partial + (size_t)split * M * N;
   const int c = lane & 31, g = lane >> 5;
