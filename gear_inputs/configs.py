@@ -36,6 +36,8 @@ class GearWorkload:
     dfv_std: float = 1.0
     refresh_every: int = 0     # full DFV refresh period in steps, 0 = never
     seed: int = 20180603
+    image_pattern: str = "zipf"  # "zipf": ids drawn per occurrence; "epoch": one image per view, every
+                                 # image exactly once per n_images / batch steps (a data set walked in epochs)
 
     @property
     def in_features(self) -> int:
@@ -75,6 +77,15 @@ WORKLOADS = {
         n_images=4_000_000, emb_dim=64, dfv_dim=1024, emb_dtype="f32", dfv_dtype="bf16",
         mlp_dtype="bf16", max_images=8, zipf_user=1.05, zipf_url=1.05, zipf_image=1.05,
         layers=(1024, 256, 1), label_p=0.03, M=16, lr=0.01, refresh_every=500),
+    # The other extreme of image reuse (Section 4.1 trains on a fixed image set split between the two
+    # gears): one image per sample, no image twice in an epoch, so a group of M closes only after M
+    # epochs and every step touches batch-many cold rows.  50,000 images as in that data set's
+    # training split; the sparse ids are few and uniform because that experiment has none.
+    "epoch": GearWorkload(
+        name="epoch", batch=5_000, steps=100, n_users=100, n_urls=128, n_images=50_000,
+        emb_dim=16, dfv_dim=256, emb_dtype="f32", dfv_dtype="f32", mlp_dtype="f32",
+        max_images=1, zipf_user=0.0, zipf_url=0.0, zipf_image=0.0,
+        layers=(256, 1), label_p=0.1, M=4, lr=0.01, image_pattern="epoch"),
 }
 
 

@@ -90,11 +90,19 @@ class PageViewSource:
         img_off = np.zeros(B + 1, dtype=np.int64)
         np.cumsum(n_img, out=img_off[1:])
         nnz = int(img_off[-1])
+        user_id = self.users.sample(rng, B)
+        url_id = self.urls.sample(rng, B)
+        if wl.image_pattern == "epoch":
+            # view b of step t shows image number (t * B + b) mod N of a fixed shuffle of the image set
+            assert wl.max_images == 1
+            img_id = self.images.rank_to_id((np.int64(step) * B + np.arange(B, dtype=np.int64)) % wl.n_images)
+        else:
+            img_id = self.images.sample(rng, nnz)
         return PageViewBatch(
-            user_id=self.users.sample(rng, B),
-            url_id=self.urls.sample(rng, B),
+            user_id=user_id,
+            url_id=url_id,
             img_off=img_off.astype(np.int32),
-            img_id=self.images.sample(rng, nnz),
+            img_id=img_id,
             label=(rng.random(B) < wl.label_p).astype(np.float32),
         )
 

@@ -115,6 +115,7 @@ class StepResult:
     grads: List[Tuple[np.ndarray, np.ndarray]]       # (dW_l, db_l)
     occ_grads: np.ndarray          # [nnz x D] dLoss/dDFV per occurrence, flat CSR order
     kink_margin: np.ndarray        # [B x hidden layers] min over the layer's units of |a| / max|a|
+    ready_term_scale: np.ndarray = field(default_factory=lambda: np.zeros(0))   # [n_ready] largest |element| of the M gradients behind each average
     user_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
     url_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
     img_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
@@ -210,6 +211,10 @@ class GearOracle:
             acc = acc + g
         return acc
 
+    def residual_term_scale(self, image_id: int) -> float:
+        """Largest |element| among the gradients currently stored for an image."""
+        return max([float(np.abs(g).max()) for g in self.store.get(int(image_id), [])] or [0.0])
+
     def receive(self, image_id: int, g: np.ndarray) -> Optional[np.ndarray]:
         """Slowgear bookkeeping for one arriving gradient (Section 1, third point; Section 3,
         step 6): keep it; once M are kept return their average and start collecting afresh."""
@@ -221,6 +226,8 @@ class GearOracle:
         total = np.zeros_like(kept[0])
         for gk in kept:                                              # arrival order
             total = total + gk
+        # size of the largest term of the average: what its rounding error is measured against
+        self.last_term_scale = max(float(np.abs(gk).max()) for gk in kept)
         kept.clear()
         return total / self.M
 
@@ -290,6 +297,7 @@ class GearOracle:
         # 5. Hand every (image id, dLoss/dDFV) to the gradient store, in flat CSR order.
         occ = np.zeros((len(img_id), D))
         emitted: List[Tuple[int, np.ndarray]] = []
+        term_scale: List[float] = []
         for b in range(B):
             n_b = off[b + 1] - off[b]
             for j in range(off[b], off[b + 1]):
@@ -297,6 +305,7 @@ class GearOracle:
                 mean = self.receive(int(img_id[j]), occ[j])
                 if mean is not None:
                     emitted.append((int(img_id[j]), mean))
+                    term_scale.append(self.last_term_scale)
 
         # 6. Ready list: ascending image id, emissions of one image in the order they happened.
         order = sorted(range(len(emitted)), key=lambda e: (emitted[e][0], e))
@@ -307,4 +316,5 @@ class GearOracle:
         return StepResult(loss=loss, ready_ids=ready_ids, ready_grads=ready_grads, x=x, logits=z,
                           dx=dx, grads=grads, occ_grads=occ, kink_margin=kink,
                           user_unique=stable_groups(user_id)[0], url_unique=stable_groups(url_id)[0],
-                          img_unique=iu, img_segoff=isegoff, img_perm=iperm)
+                          img_unique=iu, img_segoff=isegoff, img_perm=iperm,
+                          ready_term_scale=np.asarray([term_scale[e] for e in order], dtype=np.float64))

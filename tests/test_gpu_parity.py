@@ -94,7 +94,8 @@ def check_step(wl, st, orc, batch: PageViewBatch, lr: float, what: str):
     assert np.array_equal(st.ready_ids[:n_ready].cpu().numpy(), ref.ready_ids), what
     if n_ready:
         ex = np.isin(ref.ready_ids, list(flipped_imgs))
-        assert_rows_close(f64(st.ready_grads[:n_ready]), ref.ready_grads, rel, f"{what}: ready_grads", exempt=ex)
+        assert_rows_close(f64(st.ready_grads[:n_ready]), ref.ready_grads, rel, f"{what}: ready_grads", exempt=ex,
+                          term_scale=ref.ready_term_scale)
     return ref, flipped_views, flipped_imgs
 
 
@@ -111,7 +112,8 @@ def check_state(wl, st, orc, what, flipped_users=(), flipped_urls=(), flipped_im
         # images whose count is a multiple of M hold exactly zero
         full = np.array([orc.counts[i] % wl.M == 0 for i in touched])
         assert not acc[full].any(), what
-        assert_rows_close(acc, ref, rel, f"{what}: grad_accum", exempt=np.isin(touched, list(flipped_imgs)))
+        assert_rows_close(acc, ref, rel, f"{what}: grad_accum", exempt=np.isin(touched, list(flipped_imgs)),
+                          term_scale=[orc.residual_term_scale(i) for i in touched])
     # untouched accumulators are still zero
     nz_rows = int((st.grad_accum != 0).any(dim=1).sum().item())
     assert nz_rows <= len(touched), what
@@ -227,6 +229,19 @@ def test_wide_and_narrow_last_hidden_layer(dtype, hidden):
         b = src.batch(step, batch=389)
         check_step(wl, st, orc, b, 0.05, f"{dtype} hidden {hidden} step {step}")
     check_state(wl, st, orc, f"{dtype} hidden {hidden}")
+
+
+def test_epoch_pattern_free_running():
+    """One image per view, every image once per epoch: cold rows each step, groups close after M epochs."""
+    wl = get_workload("epoch").scaled(batch=600, n_images=1800, M=2)
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    emitted = []
+    for step in range(8):                                   # 2 2/3 epochs of three steps
+        ref, _, _ = check_step(wl, st, orc, src.batch(step), wl.lr, f"epoch step {step}")
+        emitted.append(len(ref.ready_ids))
+    check_state(wl, st, orc, "epoch after 8 steps")
+    assert emitted == [0, 0, 0, 600, 600, 600, 0, 0]
 
 
 def test_same_step_twice_is_bit_identical():

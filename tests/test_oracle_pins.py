@@ -439,3 +439,25 @@ def test_oracle_from_seed_uses_lazy_rows():
     assert len(o.user_emb._rows) == len(set(batch.user_id.tolist()))
     assert abs(np.std(o.dfv.rows(batch.img_id[:50])) - 1.0) < 0.05
     assert abs(np.std(o.mlp[0][0]) - math.sqrt(2 / 320)) / math.sqrt(2 / 320) < 0.02
+
+
+def test_epoch_pattern_shows_every_image_once_per_epoch():
+    """The "epoch" workload walks a fixed shuffle of the image set: no image twice before all were seen."""
+    from gear_inputs import PageViewSource, get_workload
+    wl = get_workload("epoch").scaled(batch=300, n_images=1200)
+    src = PageViewSource(wl)
+    seen = np.concatenate([src.batch(t).img_id for t in range(8)])          # two epochs of four steps
+    assert src.batch(0).nnz == 300 and np.array_equal(src.batch(3).img_off, np.arange(301))
+    for epoch in (seen[:1200], seen[1200:]):
+        assert np.array_equal(np.sort(epoch), np.arange(1200))
+    assert np.array_equal(seen[:1200], seen[1200:])                          # the same order every epoch
+    assert not np.array_equal(np.sort(seen[:300]), np.arange(300))          # shuffled, not 0..B-1
+
+
+def test_epoch_pattern_closes_groups_only_after_M_epochs():
+    from gear_inputs import PageViewSource, get_workload
+    from oracle.from_workload import oracle_for
+    wl = get_workload("epoch").scaled(batch=40, n_images=80, M=3, dfv_dim=8, emb_dim=8, layers=(8, 1))
+    orc, src = oracle_for(wl), PageViewSource(wl)
+    emitted = [len(orc.step(src.batch(t), 0.01).ready_ids) for t in range(8)]  # an epoch is two steps
+    assert emitted == [0, 0, 0, 0, 40, 40, 0, 0]
