@@ -164,6 +164,26 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *batch, gear_tabl
 gear_status gear_refresh_dfv(const gear_config *cfg, void *dfv_cache, const int32_t *image_ids,
                              const void *new_dfv, int64_t n, int32_t *status, void *stream);
 
+/* Which cached inference results a batch asks for have expired (Section 1, second point and
+ * Section 3: a cache entry is recomputed once it is older than the inference expired time;
+ * Section 4.1, Table 2: that time trades freshness for speed).  dfv_stamp [n_images] i32 (device,
+ * caller-owned) holds the time each row was last written, in the caller's unit (steps, seconds).
+ * expired_ids (device, room for n entries) receives, ascending, the distinct ids among
+ * image_ids [n] (device, a batch's flat image list) with now - dfv_stamp[id] >= expiry, and
+ * n_expired (device word) their number.  The caller recomputes those rows and hands them to
+ * gear_refresh_dfv and gear_stamp_dfv.  expiry >= 0.  status (device word, not NULL) becomes
+ * GEAR_ERR_RANGE if an id is outside [0, n_images); then n_expired is 0.  workspace as for
+ * gear_step, with max_nnz >= n. */
+gear_status gear_expired_ids(const gear_config *cfg, const int32_t *image_ids, int32_t n,
+                             const int32_t *dfv_stamp, int32_t now, int32_t expiry, void *workspace,
+                             size_t workspace_bytes, int32_t *expired_ids, int32_t *n_expired,
+                             int32_t *status, void *stream);
+
+/* dfv_stamp[image_ids[r]] = now for r < n; image_ids = NULL means rows 0..n-1.  status (device
+ * word, may be NULL) becomes GEAR_ERR_RANGE if an id is outside [0, n_images); such ids are skipped. */
+gear_status gear_stamp_dfv(const gear_config *cfg, int32_t *dfv_stamp, const int32_t *image_ids, int64_t n,
+                           int32_t now, int32_t *status, void *stream);
+
 /* Sort-by-key grouping used for the embedding updates and the per-image accumulation, exposed
  * for tests: keys [n] in [0, key_range) -> distinct keys ascending (unique [n]), segment offsets
  * (segoff [n+1]), stable permutation (perm [n]) and the number of distinct keys (n_unique [1]).

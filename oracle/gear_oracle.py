@@ -175,6 +175,8 @@ class GearOracle:
         # Section 1, third point: every gradient of an image is kept until M have arrived.
         self.store: Dict[int, List[np.ndarray]] = {}
         self.counts: Dict[int, int] = {}
+        self.stamps: Dict[int, int] = {}     # image id -> time its cached DFV was last written
+        self.stamp0 = 0                      # ... for rows never stamped
 
     # ---- construction from the counter-based initialiser ------------------------------------
     @staticmethod
@@ -203,6 +205,23 @@ class GearOracle:
         (Section 1, third point) and are not touched."""
         for i, r in zip(image_ids, np.asarray(new_rows, dtype=np.float64)):
             self.dfv.set_row(int(i), r)
+
+    # ---- expiry of cached inference results (Section 1, second point; Section 3; Table 2) ------
+    def expired(self, image_ids: Sequence[int], now: int, expiry: int) -> List[int]:
+        """The distinct images among `image_ids` whose cached DFV is at least `expiry` old, ascending.
+        A row never stamped has time `self.stamp0`."""
+        hits = set()
+        for i in image_ids:
+            i = int(i)
+            if not 0 <= i < self.dfv.n_rows:
+                raise ValueError("image id out of range")
+            if now - self.stamps.get(i, self.stamp0) >= expiry:
+                hits.add(i)
+        return sorted(hits)
+
+    def stamp(self, image_ids: Sequence[int], now: int) -> None:
+        for i in image_ids:
+            self.stamps[int(i)] = int(now)
 
     def residual(self, image_id: int) -> np.ndarray:
         """Sum of the gradients currently stored for an image (what a running sum would hold)."""

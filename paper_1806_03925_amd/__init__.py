@@ -2,7 +2,8 @@
 from .binding import (  # noqa: F401
     GEAR_BF16, GEAR_ERR_CAPACITY, GEAR_ERR_HIP, GEAR_ERR_INVALID, GEAR_ERR_RANGE, GEAR_F32, GEAR_OK,
     DeviceBatch, GearError, GearProfile, GearState, gear_config, gear_fill_normal, gear_gemm, gear_group_ids, gear_init_tables,
-    gear_mlp_param_count, gear_mlp_param_offset, gear_refresh_dfv, gear_step, gear_workspace_bytes,
+    gear_expired_ids, gear_mlp_param_count, gear_mlp_param_offset, gear_refresh_dfv, gear_stamp_dfv, gear_step,
+    gear_workspace_bytes,
     gear_workspace_region, lib, make_config,
 )
 

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
-    "gear_fill_normal", "gear_init_tables", "gear_step", "gear_refresh_dfv", "gear_group_ids",
+    "gear_fill_normal", "gear_init_tables", "gear_step", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
+    "gear_group_ids",
     "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
     "gear_status_string",
 )
@@ -79,6 +80,11 @@ def _load() -> C.CDLL:
                               C.POINTER(gear_step_out), C.c_void_p]
     lib.gear_refresh_dfv.restype = C.c_int
     lib.gear_refresh_dfv.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    lib.gear_expired_ids.restype = C.c_int
+    lib.gear_expired_ids.argtypes = [cfgp, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gear_stamp_dfv.restype = C.c_int
+    lib.gear_stamp_dfv.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.gear_group_ids.restype = C.c_int
     lib.gear_group_ids.argtypes = [cfgp, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -311,6 +317,24 @@ def gear_refresh_dfv(state: GearState, image_ids: Optional[torch.Tensor], new_df
     n = new_dfv.shape[0]
     _check(lib.gear_refresh_dfv(C.byref(state.cfg), _ptr(state.dfv_cache), _ptr(image_ids), _ptr(new_dfv), n,
                                 _ptr(state.status), _stream()), "gear_refresh_dfv")
+
+
+def gear_expired_ids(state: GearState, image_ids: torch.Tensor, dfv_stamp: torch.Tensor, now: int, expiry: int):
+    """Returns (ids buffer [n], n_expired [1]), both on the device; the first n_expired ids are valid."""
+    n = int(image_ids.numel())
+    out = torch.empty(max(n, 1), dtype=torch.int32, device=dfv_stamp.device)
+    n_out = torch.zeros(1, dtype=torch.int32, device=dfv_stamp.device)
+    _check(lib.gear_expired_ids(C.byref(state.cfg), _ptr(image_ids) if n else None, n, _ptr(dfv_stamp), int(now),
+                                int(expiry), _ptr(state.workspace), state.workspace.numel(), _ptr(out), _ptr(n_out),
+                                _ptr(state.status), _stream()), "gear_expired_ids")
+    return out, n_out
+
+
+def gear_stamp_dfv(state: GearState, dfv_stamp: torch.Tensor, image_ids: Optional[torch.Tensor], now: int,
+                   n: Optional[int] = None) -> None:
+    count = int(image_ids.numel()) if n is None and image_ids is not None else int(n if n is not None else dfv_stamp.numel())
+    _check(lib.gear_stamp_dfv(C.byref(state.cfg), _ptr(dfv_stamp), _ptr(image_ids), count, int(now), _ptr(state.status),
+                              _stream()), "gear_stamp_dfv")
 
 
 def gear_group_ids(state: GearState, keys: torch.Tensor, key_range: int):

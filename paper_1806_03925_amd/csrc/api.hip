@@ -481,6 +481,37 @@ gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t 
   return GEAR_OK;
 }
 
+gear_status gear_expired_ids(const gear_config *cfg, const int32_t *image_ids, int32_t n, const int32_t *dfv_stamp,
+                             int32_t now, int32_t expiry, void *workspace, size_t workspace_bytes,
+                             int32_t *expired_ids, int32_t *n_expired, int32_t *status, void *stream) {
+  Layout lay;
+  if (!cfg || !make_layout(*cfg, &lay) || !workspace || !dfv_stamp || !expired_ids || !n_expired || !status)
+    return GEAR_ERR_INVALID;
+  if (n < 0 || n > cfg->max_nnz || (n > 0 && !image_ids) || expiry < 0) return GEAR_ERR_INVALID;
+  if ((uintptr_t)workspace & (kAlign - 1)) return GEAR_ERR_INVALID;
+  if (workspace_bytes < lay.total) return GEAR_ERR_CAPACITY;
+  hipStream_t s = (hipStream_t)stream;
+  char *ws = (char *)workspace;
+  GEAR_HIP(launch_fill_zero(status, sizeof(int32_t), s));
+  GroupBatch gb;
+  gb.count = 1;
+  // keys are sorted on the bits of a valid id; the filter checks the range before it indexes the stamps
+  gb.p[0] = make_problem(lay, ws, 2, image_ids, n, cfg->n_images);
+  gb.p[0].pos_seg = nullptr;
+  GEAR_HIP(launch_group(gb, status, s));
+  GEAR_HIP(launch_expired(gb.p[0], dfv_stamp, cfg->n_images, now, expiry, (int32_t *)(ws + lay.tile_units), expired_ids,
+                          n_expired, status, s));
+  return GEAR_OK;
+}
+
+gear_status gear_stamp_dfv(const gear_config *cfg, int32_t *dfv_stamp, const int32_t *image_ids, int64_t n,
+                           int32_t now, int32_t *status, void *stream) {
+  if (!cfg || !config_ok(*cfg) || !dfv_stamp || n < 0) return GEAR_ERR_INVALID;
+  if (!image_ids && n > cfg->n_images) return GEAR_ERR_INVALID;
+  GEAR_HIP(launch_stamp(dfv_stamp, cfg->n_images, image_ids, n, now, status, (hipStream_t)stream));
+  return GEAR_OK;
+}
+
 gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B, int32_t M, int32_t N, int32_t K,
                       int32_t epilogue, const float *bias, const void *aux, void *out, int32_t splits,
                       float *partial, int32_t *status, void *stream) {

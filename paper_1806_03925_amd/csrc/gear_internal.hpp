@@ -162,6 +162,12 @@ hipError_t launch_validate(const gear_config &cfg, const gear_batch &b, int32_t 
                            hipStream_t s);
 
 hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t s);
+// distinct ids of a grouped list whose cache entry is older than `expiry`, ascending
+hipError_t launch_expired(const GroupProblem &img, const int32_t *stamp, int64_t n_images, int32_t now,
+                          int32_t expiry, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out, int32_t *status,
+                          hipStream_t s);
+hipError_t launch_stamp(int32_t *stamp, int64_t n_images, const int32_t *ids, int64_t n, int32_t now, int32_t *status,
+                        hipStream_t s);
 hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *occ_view,
                              const int32_t *img_off, const int32_t *counts, int32_t M, int32_t ready_cap,
                              int32_t *n_ready, int32_t *status, hipStream_t s);

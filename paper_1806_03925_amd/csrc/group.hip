@@ -352,7 +352,98 @@ __global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, Acc
   }
 }
 
+// ---- expiry of cached inference results ------------------------------------------------------------
+// The distinct image ids of a batch (segment heads of the grouping) are filtered by age and
+// compacted in order: per-tile counts, then a scatter at the tile's offset.
+__device__ __forceinline__ bool is_expired(const int32_t *__restrict__ stamp, int64_t n_images, int id, int32_t now,
+                                           int32_t expiry, int32_t *status) {
+  if (id < 0 || id >= n_images) {
+    atomicCAS(status, 0, GEAR_ERR_RANGE);
+    return false;
+  }
+  return (int64_t)now - (int64_t)stamp[id] >= (int64_t)expiry;
+}
+
+__global__ void __launch_bounds__(kSortBlock) k_expired_count(GroupProblem p, const int32_t *__restrict__ stamp,
+                                                              int64_t n_images, int32_t now, int32_t expiry,
+                                                              int32_t *__restrict__ tile_counts, int32_t *status) {
+  const int n_unique = *p.n_unique;
+  const int tile0 = blockIdx.x * kSortTile;
+  __shared__ int smem[8];
+  int c = 0;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    if (q < n_unique && is_expired(stamp, n_images, p.unique[q], now, expiry, status)) ++c;
+  }
+  int total;
+  block_exclusive_scan(c, &total, smem);
+  if (threadIdx.x == 0) tile_counts[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(kSortBlock) k_expired_scatter(GroupProblem p, const int32_t *__restrict__ stamp,
+                                                                int64_t n_images, int32_t now, int32_t expiry,
+                                                                const int32_t *__restrict__ tile_counts,
+                                                                int32_t *__restrict__ out_ids, int32_t *n_out,
+                                                                int32_t *status) {
+  const int n_unique = *p.n_unique;
+  const int tile0 = blockIdx.x * kSortTile;
+  __shared__ int smem[8];
+  const int base = sum_before(tile_counts, blockIdx.x, smem);
+  bool hit[kSortItems];
+  int c = 0;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    hit[i] = q < n_unique && is_expired(stamp, n_images, p.unique[q], now, expiry, status);
+    c += hit[i] ? 1 : 0;
+  }
+  int total;
+  int at = base + block_exclusive_scan(c, &total, smem);
+  const bool bad = *status != 0;   // set by the count pass, which saw every id: the list is then empty
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = tile0 + threadIdx.x * kSortItems + i;
+    if (hit[i] && !bad) out_ids[at] = p.unique[q];
+    at += hit[i] ? 1 : 0;
+  }
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *n_out = bad ? 0 : base + total;
+}
+
+__global__ void __launch_bounds__(256) k_stamp(int32_t *__restrict__ stamp, int64_t n_images,
+                                               const int32_t *__restrict__ ids, int64_t n, int32_t now, int32_t *status) {
+  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t id = ids ? (int64_t)ids[r] : r;
+    if (id < 0 || id >= n_images) {
+      if (status) atomicCAS(status, 0, GEAR_ERR_RANGE);
+      continue;
+    }
+    stamp[id] = now;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_expired(const GroupProblem &img, const int32_t *stamp, int64_t n_images, int32_t now,
+                          int32_t expiry, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out, int32_t *status,
+                          hipStream_t s) {
+  int tiles = (img.n + kSortTile - 1) / kSortTile;
+  if (tiles < 1) tiles = 1;
+  hipLaunchKernelGGL(k_expired_count, dim3(tiles), dim3(kSortBlock), 0, s, img, stamp, n_images, now, expiry,
+                     tile_counts, status);
+  hipLaunchKernelGGL(k_expired_scatter, dim3(tiles), dim3(kSortBlock), 0, s, img, stamp, n_images, now, expiry,
+                     tile_counts, out_ids, n_out, status);
+  return hipGetLastError();
+}
+
+hipError_t launch_stamp(int32_t *stamp, int64_t n_images, const int32_t *ids, int64_t n, int32_t now, int32_t *status,
+                        hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  int64_t want = (n + 255) / 256;
+  const int blocks = (int)(want < 4096 ? want : 4096);
+  hipLaunchKernelGGL(k_stamp, dim3(blocks), dim3(256), 0, s, stamp, n_images, ids, n, now, status);
+  return hipGetLastError();
+}
 
 hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t s) {
   int max_tiles = 1, max_passes = 0;

@@ -244,6 +244,49 @@ def test_epoch_pattern_free_running():
     assert emitted == [0, 0, 0, 600, 600, 600, 0, 0]
 
 
+def test_expired_ids_and_stamps_match_oracle():
+    """Expiry of cached inference results: bit-exact lists over several steps of refresh + stamp."""
+    wl = get_workload("hotkey").scaled(n_images=3000, batch=700)
+    cfg, st, orc = make_pair(wl)
+    stamp = torch.zeros(wl.n_images, dtype=torch.int32, device="cuda")
+    src = PageViewSource(wl)
+    total = 0
+    for now, expiry in [(0, 1), (1, 1), (2, 3), (3, 3), (4, 2), (5, 0), (9, 4)]:
+        b = src.batch(now)
+        ids = torch.from_numpy(b.img_id).cuda()
+        out, n_out = g.gear_expired_ids(st, ids, stamp, now, expiry)
+        torch.cuda.synchronize()
+        ref = orc.expired(b.img_id, now, expiry)
+        n = int(n_out.item())
+        assert int(st.status.item()) == 0 and n == len(ref), (now, expiry, n, len(ref))
+        assert np.array_equal(out[:n].cpu().numpy(), np.asarray(ref, dtype=np.int32)), (now, expiry)
+        # the caller recomputes those rows (here: fresh random rows), writes and stamps them
+        if n:
+            rows = torch.randn(n, wl.dfv_dim, device="cuda")
+            g.gear_refresh_dfv(st, out[:n], rows)
+            g.gear_stamp_dfv(st, stamp, out[:n], now)
+            orc.refresh_dfv(ref, rows.double().cpu().numpy())
+            orc.stamp(ref, now)
+        total += n
+    torch.cuda.synchronize()
+    assert total > 0
+    host = stamp.cpu().numpy()
+    assert all(host[i] == t for i, t in orc.stamps.items()) and int((host != 0).sum()) <= len(orc.stamps)
+    # refreshed rows are what the next step gathers
+    check_step(wl, st, orc, src.batch(20), wl.lr, "step after refreshes")
+    # empty request, and an id out of range
+    out, n_out = g.gear_expired_ids(st, torch.zeros(0, dtype=torch.int32, device="cuda"), stamp, 50, 0)
+    torch.cuda.synchronize()
+    assert int(n_out.item()) == 0 and int(st.status.item()) == 0
+    bad = torch.tensor([1, wl.n_images, 2], dtype=torch.int32, device="cuda")
+    out, n_out = g.gear_expired_ids(st, bad, stamp, 50, 0)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == g.GEAR_ERR_RANGE and int(n_out.item()) == 0
+    g.gear_stamp_dfv(st, stamp, None, 77)                    # all rows
+    torch.cuda.synchronize()
+    assert int((stamp != 77).sum().item()) == 0
+
+
 def test_same_step_twice_is_bit_identical():
     wl = get_workload("hotkey").scaled(n_images=500)
     outs = []

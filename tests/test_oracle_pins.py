@@ -461,3 +461,25 @@ def test_epoch_pattern_closes_groups_only_after_M_epochs():
     orc, src = oracle_for(wl), PageViewSource(wl)
     emitted = [len(orc.step(src.batch(t), 0.01).ready_ids) for t in range(8)]  # an epoch is two steps
     assert emitted == [0, 0, 0, 0, 40, 40, 0, 0]
+
+
+def test_expiry_lists_old_requested_rows_once_and_ascending():
+    """Expiry (Section 1, second point): requested and at least `expiry` old, each id once, ascending."""
+    o = small_oracle(np.random.default_rng(3))
+    n = o.dfv.n_rows
+    assert o.expired([], now=5, expiry=0) == []
+    assert o.expired([4, 1, 4, 2], now=0, expiry=0) == [1, 2, 4]          # age 0 >= 0: everything asked for
+    assert o.expired([4, 1, 4, 2], now=2, expiry=3) == []                   # never stamped = time 0: age 2 < 3
+    assert o.expired([4, 1, 4, 2], now=3, expiry=3) == [1, 2, 4]            # age == expiry counts as expired
+    o.stamp([1, 4], now=3)
+    assert o.expired([4, 1, 4, 2], now=5, expiry=3) == [2]                  # 1 and 4 are 2 old, 2 is 5 old
+    assert o.expired([4, 1, 4, 2], now=6, expiry=3) == [1, 2, 4]
+    assert o.expired([0], now=6, expiry=3) == [0]                            # only what the batch asks for is listed
+    with pytest.raises(ValueError):
+        o.expired([n], now=1, expiry=0)
+    with pytest.raises(ValueError):
+        o.expired([-1], now=1, expiry=0)
+    # stamping changes neither gradients nor counters
+    before = (dict(o.counts), {k: [g.copy() for g in v] for k, v in o.store.items()})
+    o.stamp(range(n), now=9)
+    assert before[0] == o.counts and all(np.array_equal(a, b) for k in before[1] for a, b in zip(before[1][k], o.store[k]))
