@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--cpu-sample-views", type=int, default=131072,
                     help="views of the oracle's timed sample (0 = skip the CPU baseline)")
+    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
+                    help="sgd is the workload's; adam (beta 0.9 / 0.999, eps 1e-8) is the paper's experiments' choice")
     ap.add_argument("--expiry", type=int, default=None,
                     help="instead of the periodic full refresh: before every step, recompute (here: replace by "
                          "stand-in rows) the cached DFVs the batch asks for that are at least this many steps old")
@@ -225,8 +227,12 @@ def main():
             if n:
                 g.gear_refresh_dfv(st, ids[:n], fresh_pool[:n])
                 g.gear_stamp_dfv(st, stamp, ids[:n], i)
-        g.gear_step(st, dev[i % pool], wl.M, lr)
+        if adam is None:
+            g.gear_step(st, dev[i % pool], wl.M, lr)
+        else:
+            g.gear_step_adam(st, dev[i % pool], wl.M, lr, adam)
 
+    adam = g.AdamMoments(st) if args.optimizer == "adam" else None
     it = 0
     for _ in range(W):
         one_step(it)
@@ -316,7 +322,7 @@ def main():
         "config": {"workload": wl.name, "batch": wl.batch, "n_users": wl.n_users, "n_urls": wl.n_urls,
                    "n_images": wl.n_images, "emb_dim": wl.emb_dim, "dfv_dim": wl.dfv_dim,
                    "mlp": [wl.in_features, *wl.layers], "M": wl.M, "zipf_s": wl.zipf_image,
-                   "refresh_every": refresh_every, "refresh_ms": refresh_ms, "expiry_steps": expiry,
+                   "refresh_every": refresh_every, "refresh_ms": refresh_ms, "expiry_steps": expiry, "optimizer": args.optimizer,
                    "expired_rows_per_step": refreshed_per_step,
                    "loop_ms_per_step": loop_ms / K, "profiled_ms_per_step": sum(r["ms_per_step"] for r in kernels),
                    "step_ms_p10_p50_p90": [float(np.percentile(step_ms, q)) for q in (10, 50, 90)],

@@ -156,6 +156,30 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *batch, gear_tabl
                       const void *dfv_cache, float *grad_accum, int32_t *counts, int32_t M, float lr,
                       void *workspace, size_t workspace_bytes, gear_step_out *out, void *stream);
 
+/* Adam for the Sparse Part (Section 4.1 trains with the Adam optimiser at rate 1e-4; its other
+ * constants are not given).  Kingma & Ba, Algorithm 1, at step t = 1, 2, ...:
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ *   w -= lr / (1 - beta1^t) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps).
+ * MLP parameters: every element every step; mlp_m, mlp_v are laid out like mlp_params.  Embedding
+ * rows: only the rows a step touches move, moments included (their decay is applied per touch, not
+ * per elapsed step), with the global t in the bias corrections; user_m/v and url_m/v are fp32 tables
+ * [n x emb_dim] whatever emb_dtype is.  All moment arrays are device memory, caller-owned, 16-byte
+ * aligned, zero before the first step. */
+typedef struct {
+  float beta1, beta2, eps;
+  int32_t t;                  /* this step's number, from 1 */
+  float *user_m, *user_v;     /* [n_users x emb_dim] */
+  float *url_m, *url_v;       /* [n_urls x emb_dim] */
+  float *mlp_m, *mlp_v;       /* [gear_mlp_param_count] */
+} gear_adam;
+
+/* gear_step with Adam instead of plain SGD for every parameter of the Sparse Part; adam = NULL is
+ * gear_step.  Everything else as for gear_step. */
+gear_status gear_step_adam(const gear_config *cfg, const gear_batch *batch, gear_tables *tables,
+                           const void *dfv_cache, float *grad_accum, int32_t *counts, int32_t M, float lr,
+                           const gear_adam *adam, void *workspace, size_t workspace_bytes,
+                           gear_step_out *out, void *stream);
+
 /* Overwrite cached DFVs (Section 1, second point: cached inference results are replaced after the
  * inference expired time).  Row image_ids[r] of dfv_cache becomes new_dfv[r] (device, dfv_dtype,
  * [n x dfv_dim]); image_ids = NULL means rows 0..n-1.  Ids must be distinct.  Gradient accumulators

@@ -31,7 +31,7 @@ from typing import Callable, Dict, List, Optional, Sequence, Tuple
 import numpy as np
 
 from . import philox_normal
-from .rounding import round_to
+from .rounding import round_f32, round_to
 
 STREAM_USER = 1
 STREAM_URL = 2
@@ -102,6 +102,16 @@ class RowStore:
     def rows(self, ids: Sequence[int]) -> np.ndarray:
         self.prefetch(ids)
         return np.stack([self.row(i) for i in ids]) if len(ids) else np.zeros((0, self.dim))
+
+
+@dataclass
+class AdamState:
+    """Constants, step number and moments (keyed by parameter array / table row) of Adam."""
+    beta1: float
+    beta2: float
+    eps: float
+    t: int = 0
+    moments: Dict = field(default_factory=dict)
 
 
 @dataclass
@@ -177,6 +187,7 @@ class GearOracle:
         self.counts: Dict[int, int] = {}
         self.stamps: Dict[int, int] = {}     # image id -> time its cached DFV was last written
         self.stamp0 = 0                      # ... for rows never stamped
+        self.adam: Optional[AdamState] = None   # None = plain SGD
 
     # ---- construction from the counter-based initialiser ------------------------------------
     @staticmethod
@@ -205,6 +216,26 @@ class GearOracle:
         (Section 1, third point) and are not touched."""
         for i, r in zip(image_ids, np.asarray(new_rows, dtype=np.float64)):
             self.dfv.set_row(int(i), r)
+
+    # ---- the update rule ------------------------------------------------------------------------
+    def use_adam(self, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+        """Switch from plain SGD to Adam (Section 4.1 names the optimiser, not its constants)."""
+        self.adam = AdamState(float(np.float32(beta1)), float(np.float32(beta2)), float(np.float32(eps)))
+
+    def _update(self, key, w: np.ndarray, g: np.ndarray, lr: float) -> np.ndarray:
+        """New value of the parameter array `key` (unrounded; the caller rounds to the storage type).
+        Adam as in Kingma & Ba, Algorithm 1, with moments kept in fp32; the step number is the
+        global one also for table rows, whose moments move only when the row is touched."""
+        if self.adam is None:
+            return w - lr * g
+        a = self.adam
+        m, v = a.moments.get(key, (np.zeros_like(w), np.zeros_like(w)))
+        m = round_f32(a.beta1 * m + (1.0 - a.beta1) * g)
+        v = round_f32(a.beta2 * v + (1.0 - a.beta2) * g * g)
+        a.moments[key] = (m, v)
+        step = float(np.float32(lr / (1.0 - a.beta1 ** a.t)))
+        inv_bc2 = float(np.float32(1.0 / np.sqrt(1.0 - a.beta2 ** a.t)))
+        return w - step * m / (np.sqrt(v) * inv_bc2 + a.eps)
 
     # ---- expiry of cached inference results (Section 1, second point; Section 3; Table 2) ------
     def expired(self, image_ids: Sequence[int], now: int, expiry: int) -> List[int]:
@@ -302,16 +333,22 @@ class GearOracle:
                 # dLoss/dx is never an operand of a contraction again: it stays unrounded
                 dx = back
 
-        # 4. Apply the Sparse Part's gradients (plain SGD on MLP and on the touched rows).
-        self.mlp = [(round_to(W - lr * dW, self.prec.master), round_to(b - lr * db, self.prec.master))
-                    for (W, b), (dW, db) in zip(self.mlp, grads)]
-        for table, ids, lo in ((self.user_emb, user_id, 0), (self.url_emb, url_id, d)):
+        # 4. Apply the Sparse Part's gradients: plain SGD, or Adam when `self.adam` is set (MLP: every
+        #    element; tables: the touched rows only, moments included).
+        if self.adam is not None:
+            self.adam.t += 1
+        new_mlp = []
+        for l, ((W, b), (dW, db)) in enumerate(zip(self.mlp, grads)):
+            new_mlp.append((round_to(self._update(("W", l), W, dW, lr), self.prec.master),
+                            round_to(self._update(("b", l), b, db, lr), self.prec.master)))
+        self.mlp = new_mlp
+        for name, table, ids, lo in (("user", self.user_emb, user_id, 0), ("url", self.url_emb, url_id, d)):
             row_grad: Dict[int, np.ndarray] = {}
             for b in range(B):                                       # batch order
                 k = int(ids[b])
                 row_grad[k] = row_grad.get(k, np.zeros(d)) + dx[b, lo:lo + d]
             for k, g in row_grad.items():
-                table.set_row(k, table.row(k) - lr * g)
+                table.set_row(k, self._update((name, k), table.row(k), g, lr))
 
         # 5. Hand every (image id, dLoss/dDFV) to the gradient store, in flat CSR order.
         occ = np.zeros((len(img_id), D))

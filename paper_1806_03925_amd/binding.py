@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
-    "gear_fill_normal", "gear_init_tables", "gear_step", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
+    "gear_fill_normal", "gear_init_tables", "gear_step", "gear_step_adam", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
     "gear_group_ids",
     "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
     "gear_status_string",
@@ -46,6 +46,12 @@ class gear_tables(C.Structure):
 class gear_batch(C.Structure):
     _fields_ = [("B", C.c_int32), ("nnz", C.c_int32), ("user_id", C.c_void_p), ("url_id", C.c_void_p),
                 ("img_off", C.c_void_p), ("img_id", C.c_void_p), ("label", C.c_void_p)]
+
+
+class gear_adam(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("t", C.c_int32),
+                ("user_m", C.c_void_p), ("user_v", C.c_void_p), ("url_m", C.c_void_p), ("url_v", C.c_void_p),
+                ("mlp_m", C.c_void_p), ("mlp_v", C.c_void_p)]
 
 
 class gear_step_out(C.Structure):
@@ -78,6 +84,10 @@ def _load() -> C.CDLL:
     lib.gear_step.argtypes = [cfgp, C.POINTER(gear_batch), C.POINTER(gear_tables), C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_size_t,
                               C.POINTER(gear_step_out), C.c_void_p]
+    lib.gear_step_adam.restype = C.c_int
+    lib.gear_step_adam.argtypes = [cfgp, C.POINTER(gear_batch), C.POINTER(gear_tables), C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_int32, C.c_float, C.POINTER(gear_adam), C.c_void_p, C.c_size_t,
+                                   C.POINTER(gear_step_out), C.c_void_p]
     lib.gear_refresh_dfv.restype = C.c_int
     lib.gear_refresh_dfv.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.gear_expired_ids.restype = C.c_int
@@ -311,6 +321,31 @@ def gear_step(state: GearState, batch: DeviceBatch, M: int, lr: float) -> None:
     _check(lib.gear_step(C.byref(state.cfg), C.byref(b), C.byref(t), _ptr(state.dfv_cache), _ptr(state.grad_accum),
                          _ptr(state.counts), M, lr, _ptr(state.workspace), state.workspace.numel(), C.byref(o),
                          _stream()), "gear_step")
+
+
+class AdamMoments:
+    """Device memory for gear_step_adam: zeroed moment arrays and the step counter."""
+
+    def __init__(self, state: GearState, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8):
+        cfg, dev = state.cfg, state.grad_accum.device
+        self.beta1, self.beta2, self.eps, self.t = beta1, beta2, eps, 0
+        z = lambda *shape: torch.zeros(shape, dtype=torch.float32, device=dev)
+        self.user_m, self.user_v = z(cfg.n_users, cfg.emb_dim), z(cfg.n_users, cfg.emb_dim)
+        self.url_m, self.url_v = z(cfg.n_urls, cfg.emb_dim), z(cfg.n_urls, cfg.emb_dim)
+        self.mlp_m, self.mlp_v = z(state.mlp_params.numel()), z(state.mlp_params.numel())
+
+    def as_struct(self) -> gear_adam:
+        return gear_adam(self.beta1, self.beta2, self.eps, self.t, _ptr(self.user_m), _ptr(self.user_v),
+                         _ptr(self.url_m), _ptr(self.url_v), _ptr(self.mlp_m), _ptr(self.mlp_v))
+
+
+def gear_step_adam(state: GearState, batch: DeviceBatch, M: int, lr: float, adam: AdamMoments) -> None:
+    """gear_step with Adam; advances adam.t (the step number, from 1) before the call."""
+    adam.t += 1
+    t, b, o, a = state.tables(), batch.as_struct(), state.step_out(), adam.as_struct()
+    _check(lib.gear_step_adam(C.byref(state.cfg), C.byref(b), C.byref(t), _ptr(state.dfv_cache),
+                              _ptr(state.grad_accum), _ptr(state.counts), M, lr, C.byref(a), _ptr(state.workspace),
+                              state.workspace.numel(), C.byref(o), _stream()), "gear_step_adam")
 
 
 def gear_refresh_dfv(state: GearState, image_ids: Optional[torch.Tensor], new_dfv: torch.Tensor) -> None:

@@ -1,6 +1,8 @@
 // C ABI of libgear: argument checks, workspace layout and the launch sequence of one step.
 #include "gear_internal.hpp"
 
+#include <cmath>
+
 #include <math.h>
 #include <string.h>
 
@@ -286,6 +288,13 @@ gear_status gear_init_tables(const gear_config *cfg, gear_tables *t, float *grad
 gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *t, const void *dfv_cache,
                       float *grad_accum, int32_t *counts, int32_t M, float lr, void *workspace,
                       size_t workspace_bytes, gear_step_out *out, void *stream) {
+  return gear_step_adam(cfg, b, t, dfv_cache, grad_accum, counts, M, lr, nullptr, workspace, workspace_bytes, out,
+                        stream);
+}
+
+gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tables *t, const void *dfv_cache,
+                           float *grad_accum, int32_t *counts, int32_t M, float lr, const gear_adam *adam,
+                           void *workspace, size_t workspace_bytes, gear_step_out *out, void *stream) {
   Layout lay;
   if (!cfg || !b || !t || !dfv_cache || !grad_accum || !counts || !workspace || !out) return GEAR_ERR_INVALID;
   if (!make_layout(*cfg, &lay)) return GEAR_ERR_INVALID;
@@ -300,6 +309,29 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
       !aligned16(dfv_cache) || !aligned16(t->user_emb) || !aligned16(t->url_emb))
     return GEAR_ERR_INVALID;
   if (workspace_bytes < lay.total) return GEAR_ERR_CAPACITY;
+
+  // the update rule and where each parameter array keeps its moments
+  Optim opt = {lr, 0.0f, 0.0f, 0.0f, 1.0f, 0};
+  Moments mom_mlp = {nullptr, nullptr}, mom_user = {nullptr, nullptr}, mom_url = {nullptr, nullptr};
+  if (adam) {
+    if (!(adam->beta1 >= 0.0f && adam->beta1 < 1.0f) || !(adam->beta2 >= 0.0f && adam->beta2 < 1.0f) ||
+        !(adam->eps > 0.0f) || adam->t < 1)
+      return GEAR_ERR_INVALID;
+    if (!adam->user_m || !adam->user_v || !adam->url_m || !adam->url_v || !adam->mlp_m || !adam->mlp_v)
+      return GEAR_ERR_INVALID;
+    if (!aligned16(adam->user_m) || !aligned16(adam->user_v) || !aligned16(adam->url_m) || !aligned16(adam->url_v) ||
+        !aligned16(adam->mlp_m) || !aligned16(adam->mlp_v))
+      return GEAR_ERR_INVALID;
+    opt.adam = 1;
+    opt.beta1 = adam->beta1;
+    opt.beta2 = adam->beta2;
+    opt.eps = adam->eps;
+    opt.lr = (float)((double)lr / (1.0 - pow((double)adam->beta1, (double)adam->t)));
+    opt.inv_bc2 = (float)(1.0 / sqrt(1.0 - pow((double)adam->beta2, (double)adam->t)));
+    mom_mlp = {adam->mlp_m, adam->mlp_v};
+    mom_user = {adam->user_m, adam->user_v};
+    mom_url = {adam->url_m, adam->url_v};
+  }
 
   hipStream_t s = (hipStream_t)stream;
   char *ws = (char *)workspace;
@@ -380,7 +412,8 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
            launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.w_off[L - 1],
                              t->mlp_params + lay.b_off[L - 1], t->mlp_params + lay.b_off[L - 2], b->label, B,
                              lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial),
-                             out->loss, lr, status, s));
+                             out->loss, opt, moments_at(mom_mlp, lay.w_off[L - 1]), moments_at(mom_mlp, lay.b_off[L - 1]),
+                             moments_at(mom_mlp, lay.b_off[L - 2]), status, s));
 
   // backward through the hidden layers down to dLoss/dx (all from the pre-step operand copies)
   // Each product that makes the delta of a hidden layer also leaves that layer's bias gradient (column
@@ -397,11 +430,12 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
                                          by_bits ? (const void *)relu_bits[l - 1] : (const void *)(ws + lay.h[l - 1]),
                                          ws + lay.delta[l - 1], 0, parts ? cpart : nullptr, nullptr, status, s));
       if (parts)
-        GEAR_RUN("bias_sgd", launch_partial_sgd(cpart, parts, lay.out_dim[l - 1], t->mlp_params + lay.b_off[l - 1], lr,
-                                                status, s));
+        GEAR_RUN("bias_sgd", launch_partial_sgd(cpart, parts, lay.out_dim[l - 1], t->mlp_params + lay.b_off[l - 1], opt,
+                                                moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
       else
         GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l - 1], B, lay.out_dim[l - 1], cpart,
-                                               t->mlp_params + lay.b_off[l - 1], lr, status, s));
+                                               t->mlp_params + lay.b_off[l - 1], opt,
+                                               moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
     } else {
       // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type
       GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_DX,
@@ -417,7 +451,7 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
     hipStream_t s = side->stream;
     GEAR_RUN("embedding_update",
              launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
-                                     (float *)(ws + lay.emb_partial), lr, status, s));
+                                     (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
   }
   GEAR_HIP(hipEventRecord(side->join, side->stream));
   // SGD on the hidden layers' weights: split-K wgrad (logit layer and all biases are done above)
@@ -426,7 +460,8 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
     GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
                                               lay.in_dim[l], B, splits, wpart, status, s));
     GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
-                                             t->mlp_params + lay.w_off[l], lr, status, s));
+                                             t->mlp_params + lay.w_off[l], opt, moments_at(mom_mlp, lay.w_off[l]),
+                                             status, s));
   }
 
   GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
@@ -529,7 +564,9 @@ gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B,
     if (M % vec || N % vec || splits < 1 || splits > 64 || !partial) return GEAR_ERR_INVALID;
     GEAR_HIP(launch_gemm_tn_splitk(dtype, A, B, M, N, K, splits, partial, status, s));
     GEAR_HIP(launch_fill_zero(out, (size_t)M * N * sizeof(float), s));
-    GEAR_HIP(launch_splitk_sgd(partial, splits, (int64_t)M * N, (float *)out, -1.0f, status, s));
+    const Optim minus = {-1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0};   // out = 0 - (-1) * sum of the partials
+    const Moments none = {nullptr, nullptr};
+    GEAR_HIP(launch_splitk_sgd(partial, splits, (int64_t)M * N, (float *)out, minus, none, status, s));
   } else {
     return GEAR_ERR_INVALID;
   }

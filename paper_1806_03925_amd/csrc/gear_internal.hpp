@@ -34,6 +34,32 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// How a gradient changes a parameter (Section 3, step 4 applies the Sparse Part's gradients every
+// step; Section 4.1 trains with Adam).  SGD: w -= lr g.  Adam (Kingma & Ba, Algorithm 1):
+// m = b1 m + (1 - b1) g, v = b2 v + (1 - b2) g^2, w -= lr / (1 - b1^t) * m / (sqrt(v) / sqrt(1 - b2^t) + eps);
+// the two factors that depend on t are computed by the host.
+struct Optim {
+  float lr;        // SGD: the rate.  Adam: lr / (1 - beta1^t)
+  float beta1, beta2, eps;
+  float inv_bc2;   // Adam: 1 / sqrt(1 - beta2^t)
+  int32_t adam;    // 0 = SGD
+};
+struct Moments {   // first and second moment arrays of the same shape as the parameters; null for SGD
+  float *m, *v;
+};
+__host__ __device__ __forceinline__ Moments moments_at(const Moments &base, ptrdiff_t offset) {
+  Moments r = {base.m ? base.m + offset : nullptr, base.v ? base.v + offset : nullptr};
+  return r;
+}
+__device__ __forceinline__ float optim_apply(const Optim &o, float w, float g, float *m, float *v) {
+  if (!o.adam) return w - o.lr * g;
+  const float mn = o.beta1 * *m + (1.0f - o.beta1) * g;
+  const float vn = o.beta2 * *v + (1.0f - o.beta2) * g * g;
+  *m = mn;
+  *v = vn;
+  return w - o.lr * mn / (sqrtf(vn) * o.inv_bc2 + o.eps);
+}
+
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
@@ -194,26 +220,28 @@ hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N,
 int gemm_nt_colsum_parts(int dtype, int M, int N, int K);
 bool gemm_nt_has_bits(int dtype, int K);
 // dst[j] -= lr * sum_p partial[p][j], p ascending in a fixed two-level shape
-hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, float lr, const int32_t *status,
-                              hipStream_t s);
+hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, const Optim &opt, const Moments &mom,
+                              const int32_t *status, hipStream_t s);
 // partial[z][M x N] = sum over the z-th K range of A[K x M]^T * B[K x N] (operands M-/N-contiguous).
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
                                  float *partial, const int32_t *status, hipStream_t s);
 int gemm_splitk_for(int M, int N, int K);  // wgrad split count for a [M x N] result contracted over K
-hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, float lr,
-                             const int32_t *status, hipStream_t s);
+hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, const Optim &opt,
+                             const Moments &mom, const int32_t *status, hipStream_t s);
 
 hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
                              float *bias_hidden, const float *label, int B, int H, float *logits, float *dz,
-                             void *delta, float *partials, float *loss, float lr, const int32_t *status,
+                             void *delta, float *partials, float *loss, const Optim &opt, const Moments &mom_w_last,
+                             const Moments &mom_bias_last, const Moments &mom_bias_hidden, const int32_t *status,
                              hipStream_t s);
 size_t logit_partial_floats(int H);
 
-hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, float lr,
-                             const int32_t *status, hipStream_t s);
+hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, const Optim &opt,
+                             const Moments &mom, const int32_t *status, hipStream_t s);
 
 hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
-                                   const float *dx_emb, void *user_emb, void *url_emb, float *partials, float lr,
+                                   const float *dx_emb, void *user_emb, void *url_emb, float *partials,
+                                   const Optim &opt, const Moments &mom_user, const Moments &mom_url,
                                    const int32_t *status, hipStream_t s);
 size_t embedding_partial_floats(const gear_config &cfg);
 

@@ -927,10 +927,10 @@ k_gemm_tn(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
                               partial + (size_t)blockIdx.z * M * N);
 }
 
-// W -= lr * sum_z partial[z], z ascending; a thread owns four consecutive elements (count is a
+// W <- update(W, sum_z partial[z]), z ascending; a thread owns four consecutive elements (count is a
 // multiple of 4 because layer widths are multiples of 8) and keeps eight partials in flight
 __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ partial, int splits, int64_t count,
-                                                    float *__restrict__ w, float lr,
+                                                    float *__restrict__ w, Optim opt, Moments mom,
                                                     const int32_t *__restrict__ status) {
   if (*status != 0) return;
   const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -949,7 +949,17 @@ __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ pa
     g.x += v.x, g.y += v.y, g.z += v.z, g.w += v.w;
   }
   float4 cur = *reinterpret_cast<float4 *>(w + i);
-  cur.x -= lr * g.x, cur.y -= lr * g.y, cur.z -= lr * g.z, cur.w -= lr * g.w;
+  if (!opt.adam) {
+    cur.x -= opt.lr * g.x, cur.y -= opt.lr * g.y, cur.z -= opt.lr * g.z, cur.w -= opt.lr * g.w;
+  } else {
+    float4 m = *reinterpret_cast<float4 *>(mom.m + i), v = *reinterpret_cast<float4 *>(mom.v + i);
+    cur.x = optim_apply(opt, cur.x, g.x, &m.x, &v.x);
+    cur.y = optim_apply(opt, cur.y, g.y, &m.y, &v.y);
+    cur.z = optim_apply(opt, cur.z, g.z, &m.z, &v.z);
+    cur.w = optim_apply(opt, cur.w, g.w, &m.w, &v.w);
+    *reinterpret_cast<float4 *>(mom.m + i) = m;
+    *reinterpret_cast<float4 *>(mom.v + i) = v;
+  }
   *reinterpret_cast<float4 *>(w + i) = cur;
 }
 
@@ -1050,11 +1060,11 @@ hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M,
   return hipGetLastError();
 }
 
-hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, float lr,
-                             const int32_t *status, hipStream_t s) {
+hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, const Optim &opt,
+                             const Moments &mom, const int32_t *status, hipStream_t s) {
   if (count <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_splitk_sgd, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, s, partial, splits, count,
-                     w, lr, status);
+                     w, opt, mom, status);
   return hipGetLastError();
 }
 

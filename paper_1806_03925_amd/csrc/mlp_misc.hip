@@ -267,7 +267,7 @@ k_colsum_partial(const T *__restrict__ src, int B, int H, int rows_per_chunk, fl
 // dst[j] -= lr * sum_p partial[p][j].  Eight columns per workgroup and 32 row lanes, each adding
 // every 32nd partial in order (eight loads in flight); then the 32 lanes are added in order.
 __device__ __forceinline__ void partial_sgd(const float *__restrict__ partial, int P, int H, float *__restrict__ dst,
-                                            float lr, int block) {
+                                            const Optim &opt, const Moments &mom, int block) {
   __shared__ float s[32][8];
   const int c = threadIdx.x & 7, g = threadIdx.x >> 3;
   const int j = block * 8 + c;
@@ -289,15 +289,15 @@ __device__ __forceinline__ void partial_sgd(const float *__restrict__ partial, i
     float t = 0.0f;
 #pragma unroll
     for (int k = 0; k < 32; ++k) t += s[k][c];
-    dst[j] -= lr * t;
+    dst[j] = optim_apply(opt, dst[j], t, mom.m + j, mom.v + j);
   }
 }
 
 __global__ void __launch_bounds__(256) k_partial_sgd(const float *__restrict__ partial, int P, int H,
-                                                     float *__restrict__ dst, float lr,
+                                                     float *__restrict__ dst, Optim opt, Moments mom,
                                                      const int32_t *__restrict__ status) {
   if (*status != 0) return;
-  partial_sgd(partial, P, H, dst, lr, blockIdx.x);
+  partial_sgd(partial, P, H, dst, opt, mom, blockIdx.x);
 }
 
 // Everything that follows k_logit_loss in one launch; blockIdx.y picks the job: 0 the logit layer's
@@ -305,16 +305,16 @@ __global__ void __launch_bounds__(256) k_partial_sgd(const float *__restrict__ p
 __global__ void __launch_bounds__(256)
 k_logit_finish(const float *__restrict__ part_w, const float *__restrict__ part_d, const float *__restrict__ part_b,
                const float *__restrict__ part_loss, int P, int H, int B, float *__restrict__ w_last,
-               float *__restrict__ bias_hidden, float *__restrict__ bias_last, float *__restrict__ loss, float lr,
-               const int32_t *__restrict__ status) {
+               float *__restrict__ bias_hidden, float *__restrict__ bias_last, float *__restrict__ loss, Optim opt,
+               Moments mom_w, Moments mom_bh, Moments mom_bl, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   if (blockIdx.y == 0) {
-    partial_sgd(part_w, P, H, w_last, lr, blockIdx.x);
+    partial_sgd(part_w, P, H, w_last, opt, mom_w, blockIdx.x);
   } else if (blockIdx.y == 1) {
-    partial_sgd(part_d, P, H, bias_hidden, lr, blockIdx.x);
+    partial_sgd(part_d, P, H, bias_hidden, opt, mom_bh, blockIdx.x);
   } else if (blockIdx.x == 0) {
     if (blockIdx.y == 2)
-      partial_sgd(part_b, P, 1, bias_last, lr, 0);
+      partial_sgd(part_b, P, 1, bias_last, opt, mom_bl, 0);
     else if (threadIdx.x < kWave)
       loss_final(part_loss, P, B, loss);
   }
@@ -340,7 +340,8 @@ int logit_blocks(int B) {
 // Forward logit + loss + delta of the last hidden layer, then SGD on the logit layer's weight and bias.
 hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
                              float *bias_hidden, const float *label, int B, int H, float *logits, float *dz,
-                             void *delta, float *partials, float *loss, float lr, const int32_t *status,
+                             void *delta, float *partials, float *loss, const Optim &opt, const Moments &mom_w_last,
+                             const Moments &mom_bias_last, const Moments &mom_bias_hidden, const int32_t *status,
                              hipStream_t s) {
   if (B <= 0) return hipSuccess;
   const int blocks = logit_blocks(B);
@@ -370,22 +371,22 @@ hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, floa
 #undef GEAR_LOGIT_T
 #undef GEAR_LOGIT
   hipLaunchKernelGGL(k_logit_finish, dim3((H + 7) / 8, 4), dim3(256), 0, s, part_w, part_d, part_b, part_loss, blocks,
-                     H, B, w_last, bias_hidden, bias_last, loss, lr, status);
+                     H, B, w_last, bias_hidden, bias_last, loss, opt, mom_w_last, mom_bias_hidden, mom_bias_last, status);
   return hipGetLastError();
 }
 
 size_t logit_partial_floats(int H) { return 2 * (size_t)kLossBlocks * H + 2 * (size_t)kLossBlocks; }
 
-hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, float lr, const int32_t *status,
-                              hipStream_t s) {
+hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, const Optim &opt, const Moments &mom,
+                              const int32_t *status, hipStream_t s) {
   if (P <= 0 || H <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, partial, P, H, dst, lr, status);
+  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, partial, P, H, dst, opt, mom, status);
   return hipGetLastError();
 }
 
 // dst[j] -= lr * sum_b src[b][j]   (bias gradient of a hidden layer)
-hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, float lr,
-                             const int32_t *status, hipStream_t s) {
+hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, const Optim &opt,
+                             const Moments &mom, const int32_t *status, hipStream_t s) {
   if (B <= 0 || H <= 0) return hipSuccess;
   const int chunks = (B + kColsumRows - 1) / kColsumRows;
   const int vec = dtype == GEAR_BF16 ? 8 : 4;
@@ -398,7 +399,7 @@ hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *pa
   else
     hipLaunchKernelGGL(k_colsum_partial<float>, grid, dim3(256), smem, s, (const float *)src, B, H, kColsumRows,
                        partial, status);
-  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, partial, chunks, H, dst, lr, status);
+  hipLaunchKernelGGL(k_partial_sgd, dim3((H + 7) / 8), dim3(256), 0, s, partial, chunks, H, dst, opt, mom, status);
   return hipGetLastError();
 }
 

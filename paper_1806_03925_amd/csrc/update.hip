@@ -26,26 +26,40 @@ struct Table {
   int col0;              // first column of this table's slice inside a dx row
   float *part_first;     // [chunks x d] partial of a run that began in an earlier chunk
   float *part_last;      // [chunks x d] partial of a run that begins here and goes on
+  Moments mom;           // Adam: fp32 moment tables of the same shape as `rows` (only touched rows move)
 };
 
-template <typename ET> __device__ __forceinline__ void apply_row(ET *row, int c4, float4 g, float lr);
-template <> __device__ __forceinline__ void apply_row<float>(float *row, int c4, float4 g, float lr) {
-  float4 *cell = reinterpret_cast<float4 *>(row) + c4;
-  float4 v = *cell;
-  v.x -= lr * g.x;
-  v.y -= lr * g.y;
-  v.z -= lr * g.z;
-  v.w -= lr * g.w;
-  *cell = v;
-}
-template <> __device__ __forceinline__ void apply_row<bf16_t>(bf16_t *row, int c4, float4 g, float lr) {
-  uint2 *cell = reinterpret_cast<uint2 *>(row) + c4;
-  uint2 v = *cell;
-  const float a = __uint_as_float(v.x << 16) - lr * g.x, b = __uint_as_float(v.x & 0xffff0000u) - lr * g.y;
-  const float c = __uint_as_float(v.y << 16) - lr * g.z, d = __uint_as_float(v.y & 0xffff0000u) - lr * g.w;
-  v.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-  v.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
-  *cell = v;
+// one float4 column group of a row: row <- update(row, g); mrow / vrow are the row's moments (Adam)
+template <typename ET>
+__device__ __forceinline__ void apply_row(ET *row, float *mrow, float *vrow, int c4, float4 g, const Optim &o) {
+  float4 m = make_float4(0.f, 0.f, 0.f, 0.f), v = m;
+  if (o.adam) {
+    m = reinterpret_cast<float4 *>(mrow)[c4];
+    v = reinterpret_cast<float4 *>(vrow)[c4];
+  }
+  if constexpr (sizeof(ET) == 4) {
+    float4 *cell = reinterpret_cast<float4 *>(row) + c4;
+    float4 w = *cell;
+    w.x = optim_apply(o, w.x, g.x, &m.x, &v.x);
+    w.y = optim_apply(o, w.y, g.y, &m.y, &v.y);
+    w.z = optim_apply(o, w.z, g.z, &m.z, &v.z);
+    w.w = optim_apply(o, w.w, g.w, &m.w, &v.w);
+    *cell = w;
+  } else {
+    uint2 *cell = reinterpret_cast<uint2 *>(row) + c4;
+    uint2 w = *cell;
+    const float a = optim_apply(o, __uint_as_float(w.x << 16), g.x, &m.x, &v.x);
+    const float b = optim_apply(o, __uint_as_float(w.x & 0xffff0000u), g.y, &m.y, &v.y);
+    const float c = optim_apply(o, __uint_as_float(w.y << 16), g.z, &m.z, &v.z);
+    const float d = optim_apply(o, __uint_as_float(w.y & 0xffff0000u), g.w, &m.w, &v.w);
+    w.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+    w.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+    *cell = w;
+  }
+  if (o.adam) {
+    reinterpret_cast<float4 *>(mrow)[c4] = m;
+    reinterpret_cast<float4 *>(vrow)[c4] = v;
+  }
 }
 
 __device__ __forceinline__ void add4(float4 &a, const float4 &b) {
@@ -58,7 +72,7 @@ __device__ __forceinline__ void add4(float4 &a, const float4 &b) {
 // level 1: one worker per chunk of sorted positions
 template <typename ET>
 __global__ void __launch_bounds__(256)
-k_embedding_chunks(Table users, Table urls, const float *__restrict__ dx, int F, int d, int lanes_per_worker, float lr,
+k_embedding_chunks(Table users, Table urls, const float *__restrict__ dx, int F, int d, int lanes_per_worker, Optim opt,
                    const int32_t *__restrict__ status) {
   if (*status != 0) return;
   const Table &t = blockIdx.y == 1 ? urls : users;
@@ -94,7 +108,8 @@ k_embedding_chunks(Table users, Table urls, const float *__restrict__ dx, int F,
       const bool ends_here = keys[i + 1] != keys[i];
       if (ends_here || last_in_chunk) {
         if (starts_here && ends_here) {
-          apply_row<ET>(static_cast<ET *>(t.rows) + (size_t)keys[i] * d, c4, sum, lr);
+          const size_t at = (size_t)keys[i] * d;
+          apply_row<ET>(static_cast<ET *>(t.rows) + at, t.mom.m + at, t.mom.v + at, c4, sum, opt);
         } else {
           float *dst = (starts_here ? t.part_last : t.part_first) + (size_t)chunk * d;
           *reinterpret_cast<float4 *>(dst + 4 * c4) = sum;
@@ -112,7 +127,7 @@ template <typename ET>
 __global__ void __launch_bounds__(256)
 k_embedding_spans(Table users, Table urls, const int32_t *__restrict__ user_pos_seg,
                   const int32_t *__restrict__ user_segoff, const int32_t *__restrict__ url_pos_seg,
-                  const int32_t *__restrict__ url_segoff, int d, float lr, const int32_t *__restrict__ status) {
+                  const int32_t *__restrict__ url_segoff, int d, Optim opt, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   const bool second = blockIdx.y == 1;
   const Table &t = second ? urls : users;
@@ -141,15 +156,17 @@ k_embedding_spans(Table users, Table urls, const int32_t *__restrict__ user_pos_
       for (int i = 0; i < 8; ++i) sum += v[i];
     }
     for (; k <= k_last; ++k) sum += t.part_first[(size_t)k * d + c];
-    ET *cell = static_cast<ET *>(t.rows) + (size_t)key * d + c;
-    *cell = from_f32<ET>(to_f32<ET>(*cell) - lr * sum);
+    const size_t at = (size_t)key * d + c;
+    ET *cell = static_cast<ET *>(t.rows) + at;
+    *cell = from_f32<ET>(optim_apply(opt, to_f32<ET>(*cell), sum, t.mom.m + at, t.mom.v + at));
   }
 }
 
 }  // namespace
 
 hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &users, const GroupProblem &urls,
-                                   const float *dx, void *user_emb, void *url_emb, float *partials, float lr,
+                                   const float *dx, void *user_emb, void *url_emb, float *partials,
+                                   const Optim &opt, const Moments &mom_user, const Moments &mom_url,
                                    const int32_t *status, hipStream_t s) {
   const int F = 2 * cfg.emb_dim;  // dx holds the two embedding slots of dLoss/dx only
   const int n = users.n > urls.n ? users.n : urls.n;
@@ -159,19 +176,19 @@ hipError_t launch_embedding_update(const gear_config &cfg, const GroupProblem &u
   while (lanes < d / 4) lanes <<= 1;  // power of two so that workers do not straddle wavefronts
   const int chunks = (n + kChunk - 1) / kChunk;
   const size_t per = (size_t)((cfg.max_batch + kChunk - 1) / kChunk) * d;
-  Table tu = {users.sorted_keys, users.perm, users.n, user_emb, 0, partials, partials + per};
-  Table tl = {urls.sorted_keys, urls.perm, urls.n, url_emb, d, partials + 2 * per, partials + 3 * per};
+  Table tu = {users.sorted_keys, users.perm, users.n, user_emb, 0, partials, partials + per, mom_user};
+  Table tl = {urls.sorted_keys, urls.perm, urls.n, url_emb, d, partials + 2 * per, partials + 3 * per, mom_url};
   const long long threads = (long long)chunks * lanes;
   const dim3 grid((unsigned)((threads + 255) / 256), 2);
   const dim3 grid2((chunks + 3) / 4, 2);
   if (cfg.emb_dtype == GEAR_BF16) {
-    hipLaunchKernelGGL(k_embedding_chunks<bf16_t>, grid, dim3(256), 0, s, tu, tl, dx, F, d, lanes, lr, status);
+    hipLaunchKernelGGL(k_embedding_chunks<bf16_t>, grid, dim3(256), 0, s, tu, tl, dx, F, d, lanes, opt, status);
     hipLaunchKernelGGL(k_embedding_spans<bf16_t>, grid2, dim3(256), 0, s, tu, tl, users.pos_seg, users.segoff,
-                       urls.pos_seg, urls.segoff, d, lr, status);
+                       urls.pos_seg, urls.segoff, d, opt, status);
   } else {
-    hipLaunchKernelGGL(k_embedding_chunks<float>, grid, dim3(256), 0, s, tu, tl, dx, F, d, lanes, lr, status);
+    hipLaunchKernelGGL(k_embedding_chunks<float>, grid, dim3(256), 0, s, tu, tl, dx, F, d, lanes, opt, status);
     hipLaunchKernelGGL(k_embedding_spans<float>, grid2, dim3(256), 0, s, tu, tl, users.pos_seg, users.segoff,
-                       urls.pos_seg, urls.segoff, d, lr, status);
+                       urls.pos_seg, urls.segoff, d, opt, status);
   }
   return hipGetLastError();
 }

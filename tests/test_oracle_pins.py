@@ -483,3 +483,59 @@ def test_expiry_lists_old_requested_rows_once_and_ascending():
     before = (dict(o.counts), {k: [g.copy() for g in v] for k, v in o.store.items()})
     o.stamp(range(n), now=9)
     assert before[0] == o.counts and all(np.array_equal(a, b) for k in before[1] for a, b in zip(before[1][k], o.store[k]))
+
+
+def test_adam_matches_the_library_optimisers():
+    """Adam of the Sparse Part (Section 4.1) against torch.optim.Adam (MLP) and torch.optim.SparseAdam
+    (tables: only touched rows move, global step in the bias corrections), fed the oracle's gradients."""
+    import torch
+    rng = np.random.default_rng(11)
+    o = small_oracle(rng, n_users=6, n_urls=5)
+    # an eps large enough that where it enters the formula matters
+    b1, b2, eps, lr = float(np.float32(0.9)), float(np.float32(0.999)), float(np.float32(1e-4)), 0.05
+    o.use_adam(b1, b2, eps)
+    dense = [torch.tensor(a.copy(), dtype=torch.float64, requires_grad=True) for W, b in o.mlp for a in (W, b)]
+    tables = [torch.tensor(o.user_emb._dense.copy(), dtype=torch.float64, requires_grad=True),
+              torch.tensor(o.url_emb._dense.copy(), dtype=torch.float64, requires_grad=True)]
+    opt_dense = torch.optim.Adam(dense, lr=lr, betas=(b1, b2), eps=eps)
+    opt_rows = torch.optim.SparseAdam(tables, lr=lr, betas=(b1, b2), eps=eps)
+    d = o.d
+    untouched_once = False
+    for step in range(4):
+        batch = random_batch(rng, 3, 6, 5, 9)                  # few views: some rows are skipped in a step
+        r = o.step(batch, lr)
+        for p, gnp in zip(dense, [a for dW, db in r.grads for a in (dW, db)]):
+            p.grad = torch.tensor(np.asarray(gnp, dtype=np.float64).reshape(p.shape))
+        opt_dense.step()
+        for p, ids, lo in ((tables[0], batch.user_id, 0), (tables[1], batch.url_id, d)):
+            uniq = sorted(set(int(i) for i in ids))
+            untouched_once |= len(uniq) < p.shape[0]
+            vals = np.stack([sum(r.dx[k, lo:lo + d] for k in range(batch.B) if int(ids[k]) == u) for u in uniq])
+            p.grad = torch.sparse_coo_tensor(torch.tensor([uniq]), torch.tensor(vals), p.shape).coalesce()
+        # SparseAdam writes the same update as lr sqrt(1-b2^t)/(1-b1^t) m / (sqrt(v) + eps'), eps' = eps sqrt(1-b2^t)
+        opt_rows.param_groups[0]["eps"] = eps * math.sqrt(1.0 - b2 ** (step + 1))
+        opt_rows.step()
+        got = [a for W, b in o.mlp for a in (W, b)] + [o.user_emb._dense, o.url_emb._dense]
+        for mine, ref in zip(got, dense + tables):
+            ref = ref.detach().numpy().reshape(mine.shape)
+            assert np.abs(mine - ref).max() <= 2e-6 * max(np.abs(ref).max(), lr), step   # moments are kept in fp32
+    assert untouched_once
+
+
+def test_adam_first_step_moves_every_element_by_the_rate():
+    """Closed form: at t = 1 the update is lr * g / (|g| + eps'), i.e. +-lr where |g| >> eps."""
+    rng = np.random.default_rng(5)
+    o = small_oracle(rng)
+    before = [(W.copy(), b.copy()) for W, b in o.mlp]
+    o.use_adam()
+    r = o.step(random_batch(rng, 6, 7, 5, 9), 1e-3)
+    for (W0, b0), (W1, b1), (dW, db) in zip(before, o.mlp, r.grads):
+        big = np.abs(dW) > 1e-4
+        assert big.any()
+        assert np.allclose((W0 - W1)[big], 1e-3 * np.sign(dW)[big], rtol=1e-3)
+    # plain SGD is untouched by the new code path
+    p = small_oracle(np.random.default_rng(5))
+    q = small_oracle(np.random.default_rng(5))
+    bt = random_batch(np.random.default_rng(6), 6, 7, 5, 9)
+    rp = p.step(bt, 0.1)
+    assert all(np.array_equal(W0 - 0.1 * dW, W1) for (W0, _), (W1, _), (dW, _) in zip(q.mlp, p.mlp, rp.grads))
