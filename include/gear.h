@@ -208,6 +208,38 @@ gear_status gear_expired_ids(const gear_config *cfg, const int32_t *image_ids, i
 gear_status gear_stamp_dfv(const gear_config *cfg, int32_t *dfv_stamp, const int32_t *image_ids, int64_t n,
                            int32_t now, int32_t *status, void *stream);
 
+/* A stand-in Dense Part, so that the loop of the method can be closed on one device: a linear map
+ * DFV[i] = Wd raw[i] from fixed per-image features raw [n_images x raw_dim] (f32, device) with
+ * weights Wd [dfv_dim x raw_dim] (f32, device).  Not the paper's CNN: the smallest model that has
+ * an inference pass feeding the cache (Section 3, steps 1-2) and a backward pass consuming the
+ * averaged gradients (Section 3, step 6; Eq. 1, right factor).  raw_dim and dfv_dim are multiples
+ * of 8; max_rows bounds n and n_ready of the calls below. */
+typedef struct {
+  int64_t n_images;
+  int32_t raw_dim, dfv_dim;
+  gear_dtype dfv_dtype; /* type of the rows gear_dense_infer writes (the cache's) */
+  int32_t max_rows;
+} gear_dense_config;
+
+size_t gear_dense_workspace_bytes(const gear_dense_config *cfg);
+
+/* out_rows [n x dfv_dim] (device, dfv_dtype) = Wd raw[image_ids[r]]; image_ids = NULL means images
+ * 0..n-1.  The rows are what gear_refresh_dfv takes.  workspace: gear_dense_workspace_bytes(cfg)
+ * bytes, 256-byte aligned.  status (device word, not NULL): GEAR_ERR_RANGE if an id is outside
+ * [0, n_images) (that row is then computed from image 0). */
+gear_status gear_dense_infer(const gear_dense_config *cfg, const float *raw, const float *wd,
+                             const int32_t *image_ids, int32_t n, void *out_rows, void *workspace,
+                             size_t workspace_bytes, int32_t *status, void *stream);
+
+/* Back-propagation of a step's ready list through the stand-in (Eq. 1, right factor):
+ * Wd -= lr * sum_e ready_grads[e] (outer) raw[ready_ids[e]], e < n_ready (a host count: the caller
+ * reads n_ready back first), summed in a fixed shape that depends on n_ready only.  status (device
+ * word, not NULL): GEAR_ERR_RANGE if an id is outside [0, n_images); Wd is then unchanged. */
+gear_status gear_dense_backward(const gear_dense_config *cfg, const float *raw, float *wd,
+                                const int32_t *ready_ids, const float *ready_grads, int32_t n_ready,
+                                float lr, void *workspace, size_t workspace_bytes, int32_t *status,
+                                void *stream);
+
 /* Sort-by-key grouping used for the embedding updates and the per-image accumulation, exposed
  * for tests: keys [n] in [0, key_range) -> distinct keys ascending (unique [n]), segment offsets
  * (segoff [n+1]), stable permutation (perm [n]) and the number of distinct keys (n_unique [1]).

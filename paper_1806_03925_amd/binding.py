@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
     "gear_fill_normal", "gear_init_tables", "gear_step", "gear_step_adam", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
-    "gear_group_ids",
+    "gear_dense_workspace_bytes", "gear_dense_infer", "gear_dense_backward", "gear_group_ids",
     "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
     "gear_status_string",
 )
@@ -52,6 +52,11 @@ class gear_adam(C.Structure):
     _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("t", C.c_int32),
                 ("user_m", C.c_void_p), ("user_v", C.c_void_p), ("url_m", C.c_void_p), ("url_v", C.c_void_p),
                 ("mlp_m", C.c_void_p), ("mlp_v", C.c_void_p)]
+
+
+class gear_dense_config(C.Structure):
+    _fields_ = [("n_images", C.c_int64), ("raw_dim", C.c_int32), ("dfv_dim", C.c_int32), ("dfv_dtype", C.c_int32),
+                ("max_rows", C.c_int32)]
 
 
 class gear_step_out(C.Structure):
@@ -95,6 +100,15 @@ def _load() -> C.CDLL:
                                      C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gear_stamp_dfv.restype = C.c_int
     lib.gear_stamp_dfv.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    dcp = C.POINTER(gear_dense_config)
+    lib.gear_dense_workspace_bytes.restype = C.c_size_t
+    lib.gear_dense_workspace_bytes.argtypes = [dcp]
+    lib.gear_dense_infer.restype = C.c_int
+    lib.gear_dense_infer.argtypes = [dcp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.gear_dense_backward.restype = C.c_int
+    lib.gear_dense_backward.argtypes = [dcp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float,
+                                        C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.gear_group_ids.restype = C.c_int
     lib.gear_group_ids.argtypes = [cfgp, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -370,6 +384,36 @@ def gear_stamp_dfv(state: GearState, dfv_stamp: torch.Tensor, image_ids: Optiona
     count = int(image_ids.numel()) if n is None and image_ids is not None else int(n if n is not None else dfv_stamp.numel())
     _check(lib.gear_stamp_dfv(C.byref(state.cfg), _ptr(dfv_stamp), _ptr(image_ids), count, int(now), _ptr(state.status),
                               _stream()), "gear_stamp_dfv")
+
+
+class DenseStandIn:
+    """Device memory of the stand-in Dense Part (DFV[i] = Wd raw[i]) and the two calls on it."""
+
+    def __init__(self, state: GearState, raw: torch.Tensor, wd: torch.Tensor, max_rows: int):
+        cfg = state.cfg
+        assert raw.dtype == torch.float32 and wd.dtype == torch.float32 and raw.is_contiguous() and wd.is_contiguous()
+        assert raw.shape[0] == cfg.n_images and wd.shape == (cfg.dfv_dim, raw.shape[1])
+        self.cfg = gear_dense_config(cfg.n_images, raw.shape[1], cfg.dfv_dim, cfg.dfv_dtype, max_rows)
+        self.raw, self.wd, self.state = raw, wd, state
+        nbytes = lib.gear_dense_workspace_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            raise GearError("gear_dense_workspace_bytes: invalid configuration")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=raw.device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=raw.device)
+
+    def infer(self, image_ids: Optional[torch.Tensor], n: Optional[int] = None) -> torch.Tensor:
+        """Rows [n x dfv_dim] in the cache's type for the listed images (None: images 0..n-1)."""
+        n = int(image_ids.numel()) if n is None else int(n)
+        out = torch.empty((n, self.cfg.dfv_dim), dtype=self.state.dfv_cache.dtype, device=self.raw.device)
+        _check(lib.gear_dense_infer(C.byref(self.cfg), _ptr(self.raw), _ptr(self.wd), _ptr(image_ids), n,
+                                    _ptr(out) if n else _ptr(self.workspace), _ptr(self.workspace),
+                                    self.workspace.numel(), _ptr(self.status), _stream()), "gear_dense_infer")
+        return out
+
+    def backward(self, ready_ids: torch.Tensor, ready_grads: torch.Tensor, n_ready: int, lr: float) -> None:
+        _check(lib.gear_dense_backward(C.byref(self.cfg), _ptr(self.raw), _ptr(self.wd), _ptr(ready_ids),
+                                       _ptr(ready_grads), int(n_ready), lr, _ptr(self.workspace),
+                                       self.workspace.numel(), _ptr(self.status), _stream()), "gear_dense_backward")
 
 
 def gear_group_ids(state: GearState, keys: torch.Tensor, key_range: int):

@@ -539,3 +539,48 @@ def test_adam_first_step_moves_every_element_by_the_rate():
     bt = random_batch(np.random.default_rng(6), 6, 7, 5, 9)
     rp = p.step(bt, 0.1)
     assert all(np.array_equal(W0 - 0.1 * dW, W1) for (W0, _), (W1, _), (dW, _) in zip(q.mlp, p.mlp, rp.grads))
+
+
+def test_dense_standin_gradient_is_the_chain_rule_of_eq1():
+    """Eq. 1: dLoss/dWd = dLoss/dDFV * dDFV/dWd.  With M = 1 every occurrence is emitted at once, so the
+    stand-in's weight change over one step is -lr times the derivative of the Sparse Part's loss with
+    respect to Wd when the cache holds Wd raw[i]; checked by central finite differences on the loss."""
+    from oracle.dense_standin import DenseStandIn
+    rng = np.random.default_rng(21)
+    n_images, D, r = 9, 3, 4
+    raw, wd0 = rng.normal(0, 1, (n_images, r)), rng.normal(0, 0.5, (D, r))
+
+    batch = random_batch(np.random.default_rng(5), 6, 7, 5, n_images)
+    o = small_oracle(np.random.default_rng(77), n_images=n_images, D=D, M=1)
+    dense = DenseStandIn(raw, wd0, "f64")
+    dense.raw, dense.wd = np.asarray(raw, np.float64), np.asarray(wd0, np.float64)   # unrounded, for the check
+    o.refresh_dfv(range(n_images), dense.infer(range(n_images)))
+    res = o.step(batch, 0.0)
+    before = dense.wd.copy()
+    dense.backward(res.ready_ids, res.ready_grads, 1.0)
+    analytic = before - dense.wd                                      # lr = 1: the gradient itself (fp32-rounded)
+    h = 1e-6
+    for (a, b) in [(0, 0), (1, 2), (2, 3), (0, 1)]:
+        vals = []
+        for sgn in (+1, -1):
+            wd = np.array(wd0, dtype=np.float64)
+            wd[a, b] += sgn * h
+            oo = small_oracle(np.random.default_rng(77), n_images=n_images, D=D, M=1)
+            oo.refresh_dfv(range(n_images), np.asarray(raw, np.float64) @ wd.T)
+            vals.append(oo.step(batch, 0.0).loss)
+        numeric = (vals[0] - vals[1]) / (2 * h)
+        assert abs(numeric - analytic[a, b]) <= 1e-6 * max(1.0, abs(numeric)) + 1e-7, (a, b, numeric, analytic[a, b])
+    # the steps per emission add up to one step with the summed outer products
+    total = sum(np.outer(g, raw[int(i)]) for i, g in zip(res.ready_ids, res.ready_grads))
+    assert np.allclose(analytic, total, rtol=0, atol=1e-6 * np.abs(total).max() + 1e-7)
+
+
+def test_dense_standin_infer_rounds_to_the_cache_type():
+    from oracle.dense_standin import DenseStandIn
+    rng = np.random.default_rng(2)
+    dense = DenseStandIn(rng.normal(0, 1, (5, 8)), rng.normal(0, 1, (3, 8)), "bf16")
+    rows = dense.infer([4, 0, 4])
+    assert np.array_equal(rows, round_bf16(rows)) and np.array_equal(rows[0], rows[2])
+    assert np.allclose(rows[1], dense.wd @ dense.raw[0], rtol=2 ** -8)
+    with pytest.raises(ValueError):
+        dense.infer([5])
