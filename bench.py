@@ -40,6 +40,9 @@ def parse_args():
                     help="views of the oracle's timed sample (0 = skip the CPU baseline)")
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
                     help="sgd is the workload's; adam (beta 0.9 / 0.999, eps 1e-8) is the paper's experiments' choice")
+    ap.add_argument("--dense-raw-dim", type=int, default=0,
+                    help="close the loop with the stand-in Dense Part (DFV = Wd raw, raw of this width): its backward "
+                         "pass takes every step's ready list, its inference pass replaces the periodic refresh")
     ap.add_argument("--expiry", type=int, default=None,
                     help="instead of the periodic full refresh: before every step, recompute (here: replace by "
                          "stand-in rows) the cached DFVs the batch asks for that are at least this many steps old")
@@ -231,8 +234,19 @@ def main():
             g.gear_step(st, dev[i % pool], wl.M, lr)
         else:
             g.gear_step_adam(st, dev[i % pool], wl.M, lr, adam)
+        if dense is not None:
+            n_ready = int(st.n_ready.item())           # the Dense Part's caller has to know how many arrived
+            dense.backward(st.ready_ids, st.ready_grads, n_ready, lr)
 
     adam = g.AdamMoments(st) if args.optimizer == "adam" else None
+    dense, dense_rows = None, 1 << 18
+    if args.dense_raw_dim:
+        R = args.dense_raw_dim
+        raw = torch.empty((wl.n_images, R), dtype=torch.float32, device="cuda")
+        wd = torch.empty((wl.dfv_dim, R), dtype=torch.float32, device="cuda")
+        g.gear_fill_normal(raw, wl.n_images, R, wl.seed + 3, 3, 1.0)
+        g.gear_fill_normal(wd, wl.dfv_dim, R, wl.seed + 4, 3, R ** -0.5)
+        dense = g.DenseStandIn(st, raw, wd, max_rows=max(dense_rows, wl.max_nnz))
     it = 0
     for _ in range(W):
         one_step(it)
@@ -271,7 +285,7 @@ def main():
     st.profile = None
 
     # the workload's periodic full DFV refresh (new vectors stand in for a Dense-Part inference pass)
-    refresh_ms, copy_gbs = 0.0, None
+    refresh_ms, copy_gbs, dense_refresh_ms = 0.0, None, None
     refresh_every = 0 if expiry is not None else wl.refresh_every   # expiry mode replaces the periodic full refresh
     if wl.refresh_every:
         fresh = torch.empty_like(st.dfv_cache)
@@ -281,13 +295,25 @@ def main():
         e0.record()
         g.gear_refresh_dfv(st, None, fresh)
         e1.record()
+        if dense is not None:
+            # the refresh as the closed loop does it: inference for the whole image set, a slab at a time
+            d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            d0.record()
+            for c0 in range(0, wl.n_images, dense_rows):
+                ids = torch.arange(c0, min(wl.n_images, c0 + dense_rows), dtype=torch.int32, device="cuda")
+                g.gear_refresh_dfv(st, ids, dense.infer(ids))
+            d1.record()
+            torch.cuda.synchronize()
+            dense_refresh_ms = d0.elapsed_time(d1)
         torch.cuda.synchronize()
         refresh_ms = e0.elapsed_time(e1)
         # the refresh is a plain copy of the whole cache: what this device's HBM sustains in practice
         copy_gbs = 2.0 * wl.n_images * wl.dfv_dim * BYTES[wl.dfv_dtype] / (refresh_ms * 1e-3) / 1e9
         del fresh
 
-    ms_per_step = loop_ms / K + (refresh_ms / refresh_every if refresh_every else 0.0)
+    per_refresh = dense_refresh_ms if dense_refresh_ms is not None else refresh_ms
+    ms_per_step = loop_ms / K + (per_refresh / refresh_every if refresh_every else 0.0)
     value = wl.batch / (ms_per_step * 1e-3)
 
     kernels = []
@@ -323,6 +349,7 @@ def main():
                    "n_images": wl.n_images, "emb_dim": wl.emb_dim, "dfv_dim": wl.dfv_dim,
                    "mlp": [wl.in_features, *wl.layers], "M": wl.M, "zipf_s": wl.zipf_image,
                    "refresh_every": refresh_every, "refresh_ms": refresh_ms, "expiry_steps": expiry, "optimizer": args.optimizer,
+                   "dense_raw_dim": args.dense_raw_dim or None, "dense_refresh_ms": dense_refresh_ms,
                    "expired_rows_per_step": refreshed_per_step,
                    "loop_ms_per_step": loop_ms / K, "profiled_ms_per_step": sum(r["ms_per_step"] for r in kernels),
                    "step_ms_p10_p50_p90": [float(np.percentile(step_ms, q)) for q in (10, 50, 90)],
