@@ -93,7 +93,7 @@ TRAFFIC_KERNELS = {
     "accumulate": ("k_accumulate", 1, 0, ["accum.hip"]),
     "fwd_gemm_l0": ("k_gemm_nt_dma<0>", 2, 0, ["gemm.hip"]),
     "fwd_gemm_l1": ("k_gemm_nt_dma<0>", 2, 1, ["gemm.hip"]),
-    "dgrad_gemm_l1": ("k_gemm_nt_dma<1>", 1, 0, ["gemm.hip"]),
+    "dgrad_gemm_l1": ("k_gemm_nt_dma<4>", 1, 0, ["gemm.hip"]),   # masked by the sign bitmap
     "dgrad_gemm_l0": ("k_gemm_nt_dma<3>", 1, 0, ["gemm.hip"]),
     "wgrad_gemm_l1": ("k_gemm_tn_dma", 2, 0, ["gemm.hip"]),
     "wgrad_gemm_l0": ("k_gemm_tn_dma", 2, 1, ["gemm.hip"]),
