@@ -7,10 +7,12 @@
 //
 // bf16, K a multiple of 32 (every workload): one workgroup = 8 wavefronts (2 x 4) on a 256 x 256
 // block tile, a wavefront owns 128 x 64 as 4 x 2 MFMA 32x32x16 tiles.  Operand tiles of k-depth 32
-// are copied global -> LDS by DMA (global_load_lds_dwordx4) into four stages, two tiles in flight
-// while one is multiplied, one s_barrier per k-tile.  NT form: LDS rows are [row][32 k] with the four
-// 16-byte k-pieces XOR-swizzled by the row so that ds_read_b128 operand fetches do not conflict.
-// TN form (wgrad): LDS keeps the global [k][row] order and ds_read_b64_tr_b16 assembles the operand.
+// are copied global -> LDS by DMA (global_load_lds_dwordx4) into four stages.  NT form: two k-tiles
+// are copied together while the two before them are multiplied (the halves of a 128-byte line then
+// meet in the vector cache), one wait and one s_barrier per pair; LDS rows are [row][32 k] with the
+// four 16-byte k-pieces XOR-swizzled by the row so that ds_read_b128 operand fetches do not conflict.
+// TN form (wgrad): one k-tile per barrier, two in flight; LDS keeps the global [k][row] order and
+// ds_read_b64_tr_b16 assembles the operand.
 // bf16 results leave through a per-wave LDS patch so that every lane stores 16 contiguous bytes.
 // Consecutive workgroup ids are spread over the eight XCDs by the hardware; the tile index is
 // remapped so that workgroups on one XCD walk neighbouring tiles and share operands in its L2.

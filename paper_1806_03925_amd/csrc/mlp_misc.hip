@@ -38,11 +38,10 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-constexpr int kMaxVecPerLane = 4;  // a lane owns up to 4 16-byte pieces of a row: H <= 2048 (bf16) / 1024 (fp32)
 
-// Logit layer, loss and everything that hangs on dLoss/dz.  One wavefront per view, a workgroup
-// owns a contiguous range of views and its waves take them round-robin, so every sum below has a
-// shape fixed by B alone:
+// Logit layer, loss and everything that hangs on dLoss/dz.  A workgroup owns a contiguous range of
+// views and its lane groups take them in a fixed pattern, so every sum below has a shape fixed by
+// B alone:
 //   z = h . w + b,  loss term,  dz = (sigmoid(z) - y) / B,
 //   delta[b, j] = dz * w[j] * [h[b, j] > 0]                      (delta of the last hidden layer)
 //   part_w[block][j] = sum_b dz_b h[b, j],  part_b[block] = sum_b dz_b,  part_loss[block] = sum_b loss_b
