@@ -180,7 +180,7 @@ def cpu_baseline(wl, views):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+        print(f"bench.py: this library runs on one GPU only (got --gpus {args.gpus}); "
               "the step has no multi-GPU path", file=sys.stderr)
         sys.exit(2)
 
