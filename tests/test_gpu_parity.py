@@ -89,7 +89,9 @@ def check_step(wl, st, orc, batch: PageViewBatch, lr: float, what: str, adam=Non
         cap = max(2, flip_cap * B)
     assert failed.sum() <= cap, f"{what}: {failed.sum()} of {B} dx rows flipped at kinks ({near_kink.sum()} rows are near one)"
     assert np.median(err / scale) <= rel / 4, f"{what}: median dx row error {np.median(err / scale):.2e}"
-    flipped_views = np.flatnonzero(failed)
+    # downstream sums inherit a view's error: views at more than half the bar (far above the rounding
+    # noise of a view with no flipped unit) are treated like the failed ones when rows are exempted
+    flipped_views = np.flatnonzero(err > 0.5 * rel * scale)
     flipped_imgs = set()
     for b in flipped_views:
         flipped_imgs.update(batch.img_id[batch.img_off[b]:batch.img_off[b + 1]].tolist())
@@ -414,6 +416,23 @@ def test_dense_standin_closes_the_loop(name):
     dense.backward(bad, st.ready_grads, 2, 0.5)
     torch.cuda.synchronize()
     assert int(dense.status.item()) == g.GEAR_ERR_RANGE and torch.equal(before, dense.wd)
+
+
+def test_large_workload_at_full_size():
+    """The benchmark's own configuration: 50 M users, 2^25 URL buckets, 4 M images with 1024-wide bf16
+    DFVs, B = 65 536, the launch shapes bench.py times.  The oracle materialises only the rows the two
+    steps touch; every output and every touched row of the 46 GB of state is compared."""
+    wl = get_workload("large")
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    fu, fl, fi = set(), set(), set()
+    for step in range(2):
+        b = src.batch(step)
+        assert b.B == 65536
+        ref, fv, imgs = check_step(wl, st, orc, b, wl.lr, f"large full size step {step}", earlier_flipped_imgs=fi)
+        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
+    check_state(wl, st, orc, "large full size", fu, fl, fi)
+    assert int(st.n_ready.item()) > 10_000
 
 
 def test_same_step_twice_is_bit_identical():
