@@ -35,30 +35,22 @@ template <> struct Cols<bf16_t> {
   }
 };
 
-// Accumulator rows and emitted averages are touched once per step: they are read and written with the
-// non-temporal hint so that they do not push the dLoss/dx rows, which are read several times, out of
-// the caches.
-typedef float f32x4_nt __attribute__((ext_vector_type(4)));
 template <int N> __device__ __forceinline__ void load_f32(const float *p, float (&v)[N]) {
 #pragma unroll
   for (int k = 0; k < N; k += 4) {
-    const f32x4_nt t = *reinterpret_cast<const f32x4_nt *>(p + k);
+    const float4 t = *reinterpret_cast<const float4 *>(p + k);
     v[k] = t.x, v[k + 1] = t.y, v[k + 2] = t.z, v[k + 3] = t.w;
   }
 }
 template <int N> __device__ __forceinline__ void store_f32(float *p, const float (&v)[N], float scale) {
 #pragma unroll
-  for (int k = 0; k < N; k += 4) {
-    const f32x4_nt t = {v[k] * scale, v[k + 1] * scale, v[k + 2] * scale, v[k + 3] * scale};
-    __builtin_nontemporal_store(t, reinterpret_cast<f32x4_nt *>(p + k));
-  }
+  for (int k = 0; k < N; k += 4)
+    *reinterpret_cast<float4 *>(p + k) = make_float4(v[k] * scale, v[k + 1] * scale, v[k + 2] * scale, v[k + 3] * scale);
 }
 template <int N> __device__ __forceinline__ void store_div(float *p, const float (&v)[N], float by) {
 #pragma unroll
-  for (int k = 0; k < N; k += 4) {
-    const f32x4_nt t = {v[k] / by, v[k + 1] / by, v[k + 2] / by, v[k + 3] / by};
-    __builtin_nontemporal_store(t, reinterpret_cast<f32x4_nt *>(p + k));
-  }
+  for (int k = 0; k < N; k += 4)
+    *reinterpret_cast<float4 *>(p + k) = make_float4(v[k] / by, v[k + 1] / by, v[k + 2] / by, v[k + 3] / by);
 }
 
 // acc += sum over sorted positions [qa, qb) of dx[view(q)][col ..] / n_view, in order; eight rows in flight
