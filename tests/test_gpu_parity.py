@@ -435,6 +435,39 @@ def test_large_workload_at_full_size():
     assert int(st.n_ready.item()) > 10_000
 
 
+def test_integer_outputs_over_many_steps():
+    """Counts and ready lists over 40 steps against their definition (Section 1, third point): an image
+    whose gradient count passes k multiples of M in a step appears k times; lists ascend by id."""
+    wl = get_workload("hotkey").scaled(n_images=400, M=8, n_users=5000, n_urls=4096)
+    batch = 1500
+    cfg = g.config_for(wl, max_batch=batch)
+    st = g.GearState(cfg, debug=True)
+    g.gear_init_tables(st)
+    g.gear_fill_normal(st.dfv_cache, wl.n_images, wl.dfv_dim, wl.seed, 3, wl.dfv_std)
+    src = PageViewSource(wl)
+    counts = np.zeros(wl.n_images, dtype=np.int64)
+    total_ready = 0
+    for step in range(40):
+        b = src.batch(step, batch=batch)
+        g.gear_step(st, g.DeviceBatch.from_host(b), wl.M, wl.lr)
+        n_i = np.bincount(b.img_id, minlength=wl.n_images)
+        emits = (counts + n_i) // wl.M - counts // wl.M
+        counts += n_i
+        expect = np.repeat(np.arange(wl.n_images, dtype=np.int32), emits)
+        torch.cuda.synchronize()
+        assert int(st.status.item()) == 0
+        n = int(st.n_ready.item())
+        assert n == len(expect), (step, n, len(expect))
+        assert np.array_equal(st.ready_ids[:n].cpu().numpy(), expect), step
+        assert np.array_equal(st.counts.cpu().numpy(), counts.astype(np.int32)), step
+        assert np.isfinite(float(st.loss.item())) and torch.isfinite(st.ready_grads[:n]).all()
+        total_ready += n
+    # accumulators of images whose count is a multiple of M are exactly zero again
+    acc_nz = (st.grad_accum != 0).any(dim=1).cpu().numpy()
+    assert not acc_nz[counts % wl.M == 0].any() and acc_nz[counts % wl.M != 0].all()
+    assert total_ready == int((counts // wl.M).sum())
+
+
 def test_same_step_twice_is_bit_identical():
     wl = get_workload("hotkey").scaled(n_images=500)
     outs = []
