@@ -468,6 +468,20 @@ def test_integer_outputs_over_many_steps():
     assert total_ready == int((counts // wl.M).sum())
 
 
+@pytest.mark.parametrize("emb,dfv,mlp", [(e, d, m) for e in ("f32", "bf16") for d in ("f32", "bf16") for m in ("f32", "bf16")])
+def test_every_combination_of_storage_types(emb, dfv, mlp):
+    """Tables, cache and MLP operands each in fp32 or bf16: all eight gather / update variants."""
+    wl = get_workload("tiny").scaled(emb_dtype=emb, dfv_dtype=dfv, mlp_dtype=mlp, layers=(64, 32, 1), M=3)
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    fu, fl, fi = set(), set(), set()
+    for step in range(2):
+        b = src.batch(step, batch=300)
+        ref, fv, imgs = check_step(wl, st, orc, b, 0.5, f"{emb}/{dfv}/{mlp} step {step}", earlier_flipped_imgs=fi)
+        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
+    check_state(wl, st, orc, f"{emb}/{dfv}/{mlp}", fu, fl, fi)
+
+
 def test_same_step_twice_is_bit_identical():
     wl = get_workload("hotkey").scaled(n_images=500)
     outs = []
