@@ -1,9 +1,9 @@
 // Sparse-Part input: x_b = [user_emb[user_b] | url_emb[url_b] | mean of the view's cached DFVs].
 //
 // The Dense Part is not evaluated during a step; its outputs are fetched from the cache by image
-// id (Section 1, second point; Section 3, steps 1-3).  How the DFVs of a view's several images
-// (Section 1: "multiple Image ID for one page view") meet the sparse features is in the paper's
-// lost model figure; the workloads fix it as a mean over the view's images.
+// id (Section 1, second point; Section 3, steps 1-3).  A page view carries several image ids
+// (Section 1); how their DFVs meet the sparse features is in the paper's lost model figure, and is
+// taken here as a mean over the view's images.
 //
 // One wavefront per page view.  A lane owns 16-byte pieces of the row, so a DFV row is read with
 // fully coalesced 1 KB wave loads, several images in flight; the sum runs in fp32 in CSR order.
