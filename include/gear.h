@@ -53,7 +53,7 @@ typedef enum gear_dtype { GEAR_F32 = 0, GEAR_BF16 = 1 } gear_dtype;
  * F = 2*emb_dim + dfv_dim, followed by n_layers affine layers of output widths
  * layer_out[0..n_layers-1] with ReLU between them; the last width must be 1 (the
  * logit).  Requirements: 2 <= n_layers <= GEAR_MAX_LAYERS, emb_dim % 8 == 0,
- * dfv_dim % 8 == 0, hidden widths % 8 == 0. */
+ * dfv_dim % 8 == 0, hidden widths % 8 == 0, last hidden width <= 1024, table sizes below 2^31. */
 typedef struct gear_config {
   int64_t n_users, n_urls, n_images;
   int32_t emb_dim, dfv_dim;
@@ -104,8 +104,8 @@ typedef struct gear_step_out {
    * permutation perm is perm[segoff[s] .. segoff[s+1]), flat CSR positions ascending. */
   int32_t *dbg_img_unique, *dbg_img_segoff, *dbg_img_perm, *dbg_n_img_unique;
   /* Optional timing (NULL = off): a gear_profile from gear_profile_create.  Every kernel launch of
-   * the step is then bracketed by HIP events on `stream`; read them with gear_profile_span after
-   * synchronising the stream. */
+   * the step is then bracketed by HIP events on the stream it is launched on (the caller's or the
+   * helper stream); read them with gear_profile_span after synchronising the caller's stream. */
   void *profile;
 } gear_step_out;
 
