@@ -17,7 +17,9 @@
  * forked from and joined back into the caller's stream).  Calls enqueue their
  * kernels on the given hipStream_t (passed as void*) and return without
  * synchronising.  Results are valid once the caller has synchronised that
- * stream.  Steps on one device must not overlap each other.
+ * stream.  The stream must belong to the current device.  Steps on one device
+ * must not overlap each other; the entry points may be called from several
+ * host threads (one per device, say).
  *
  * Errors.  Everything the host can check (NULL pointers, dimensions, M < 1,
  * sizes over the configured maxima, a workspace that is too small) is reported

@@ -1,11 +1,10 @@
 // C ABI of libgear: argument checks, workspace layout and the launch sequence of one step.
 #include "gear_internal.hpp"
 
-#include <cmath>
-
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 namespace gear {
@@ -188,17 +187,30 @@ struct SideLane {
   bool ready = false;
 };
 SideLane g_side[64];
+std::mutex g_side_mutex;
 
+// the helper lane of the current device; nullptr when one of its objects cannot be created (nothing
+// half-made is kept: the next call starts over)
 SideLane *side_lane() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_side_mutex);
   SideLane &l = g_side[dev];
   if (!l.ready) {
-    if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&l.join, hipEventDisableTiming) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&l.cast, hipEventDisableTiming) != hipSuccess) return nullptr;
-    l.ready = true;
+    SideLane made;
+    bool ok = hipStreamCreateWithFlags(&made.stream, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&made.fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&made.join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&made.cast, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+      if (made.cast) (void)hipEventDestroy(made.cast);
+      if (made.join) (void)hipEventDestroy(made.join);
+      if (made.fork) (void)hipEventDestroy(made.fork);
+      if (made.stream) (void)hipStreamDestroy(made.stream);
+      return nullptr;
+    }
+    made.ready = true;
+    l = made;
   }
   return &l;
 }
@@ -577,12 +589,16 @@ gear_profile *gear_profile_create(void) {
   gear_profile *p = new (std::nothrow) gear_profile;
   if (!p) return nullptr;
   p->used = 0;
-  for (int i = 0; i < gear_profile::kMaxSpans; ++i) {
+  int made = 0;  // events created so far, start[0], stop[0], start[1], ...
+  for (; made < 2 * gear_profile::kMaxSpans; ++made) {
+    const int i = made / 2;
     p->name[i] = "";
-    if (hipEventCreate(&p->start[i]) != hipSuccess || hipEventCreate(&p->stop[i]) != hipSuccess) {
-      delete p;  // events created so far are released with the context
-      return nullptr;
-    }
+    if (hipEventCreate(made % 2 ? &p->stop[i] : &p->start[i]) != hipSuccess) break;
+  }
+  if (made < 2 * gear_profile::kMaxSpans) {
+    for (int e = 0; e < made; ++e) (void)hipEventDestroy(e % 2 ? p->stop[e / 2] : p->start[e / 2]);
+    delete p;
+    return nullptr;
   }
   return p;
 }
