@@ -152,8 +152,9 @@ gear_status gear_init_tables(const gear_config *cfg, gear_tables *tables, float 
  *     unfinished one stays summed in grad_accum[i];  counts[i] += occurrences of i.
  * dfv_cache [n_images x dfv_dim] (dfv_dtype) is read only.  grad_accum [n_images x dfv_dim] f32 and
  * counts [n_images] i32 must be the arrays given to gear_init_tables and M must not change over
- * their life.  workspace: gear_workspace_bytes(cfg) bytes, 256-byte aligned.  Results do not
- * depend on the order in which the device schedules its work. */
+ * their life.  workspace: gear_workspace_bytes(cfg) bytes, 256-byte aligned; the tables,
+ * mlp_params, dfv_cache, grad_accum and ready_grads 16-byte aligned.  Results do not depend on the
+ * order in which the device schedules its work. */
 gear_status gear_step(const gear_config *cfg, const gear_batch *batch, gear_tables *tables,
                       const void *dfv_cache, float *grad_accum, int32_t *counts, int32_t M, float lr,
                       void *workspace, size_t workspace_bytes, gear_step_out *out, void *stream);

@@ -318,7 +318,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   if (b->B > 0 && (!b->user_id || !b->url_id || !b->img_off || !b->label)) return GEAR_ERR_INVALID;
   if (b->nnz > 0 && (!b->img_id || b->B == 0)) return GEAR_ERR_INVALID;
   if (((uintptr_t)workspace & (kAlign - 1)) || !aligned16(grad_accum) || !aligned16(out->ready_grads) ||
-      !aligned16(dfv_cache) || !aligned16(t->user_emb) || !aligned16(t->url_emb))
+      !aligned16(dfv_cache) || !aligned16(t->user_emb) || !aligned16(t->url_emb) || !aligned16(t->mlp_params))
     return GEAR_ERR_INVALID;
   if (workspace_bytes < lay.total) return GEAR_ERR_CAPACITY;
 
