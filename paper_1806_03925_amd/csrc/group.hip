@@ -75,8 +75,11 @@ __global__ void __launch_bounds__(kSortBlock) k_radix_hist(GroupBatch gb, int pa
 }
 
 // ---- radix pass: offsets over tiles.  block_hist[t][d] becomes the number of keys with digit d in
-// tiles before t; row n_tiles receives the total of digit d.  One workgroup per 64 digits; its four
-// waves split the tiles into four contiguous ranges (integer sums: any shape gives the same result).
+// tiles before t; row n_tiles receives the total of digit d.  One workgroup per 64 digits (a lane
+// owns a digit); its four waves split a chunk of up to 128 tiles into four contiguous ranges and
+// hold their part in registers, so all loads of a chunk are in flight together and nothing is read
+// twice (integer sums: any shape gives the same result).
+constexpr int kScanPerWave = 32;  // tiles a wave holds at a time
 __global__ void __launch_bounds__(256) k_radix_scan(GroupBatch gb, int pass, const int32_t *status) {
   if (*status != 0) return;
   const GroupProblem &p = gb.p[blockIdx.y];
@@ -85,43 +88,67 @@ __global__ void __launch_bounds__(256) k_radix_scan(GroupBatch gb, int pass, con
   __shared__ int range_sum[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d = blockIdx.x * 64 + lane;
+  const bool live = d < radix;
   const int n_tiles = (p.n + kSortTile - 1) / kSortTile;
-  const int per = (n_tiles + 3) / 4;
-  const int t0 = min(n_tiles, wave * per), t1 = min(n_tiles, t0 + per);
-  int32_t *col = p.block_hist + d;
-  int sum = 0;
-  if (d < radix)
-    for (int t = t0; t < t1; ++t) sum += col[(size_t)t * radix];
-  range_sum[wave][lane] = sum;
-  __syncthreads();
-  int run = 0;
-  for (int w = 0; w < wave; ++w) run += range_sum[w][lane];
-  if (d < radix) {
-    for (int t = t0; t < t1; ++t) {
-      const int c = col[(size_t)t * radix];
-      col[(size_t)t * radix] = run;
-      run += c;
+  int32_t *col = p.block_hist + (live ? d : 0);
+  int carry = 0;  // keys with this digit in the chunks before
+  for (int c0 = 0; c0 < n_tiles; c0 += 4 * kScanPerWave) {
+    const int chunk = min(n_tiles - c0, 4 * kScanPerWave);
+    const int per = (chunk + 3) / 4;
+    const int t0 = c0 + min(chunk, wave * per), t1 = c0 + min(chunk, (wave + 1) * per);
+    int v[kScanPerWave];
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerWave; ++i) {
+      v[i] = (live && t0 + i < t1) ? col[(size_t)(t0 + i) * radix] : 0;
+      sum += v[i];
     }
-    if (wave == 3) col[(size_t)n_tiles * radix] = run;  // the last range ends with the digit's total
+    __syncthreads();  // range_sum may still be read from the chunk before
+    range_sum[wave][lane] = sum;
+    __syncthreads();
+    int run = carry, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int r = range_sum[w][lane];
+      if (w < wave) run += r;
+      total += r;
+    }
+    carry += total;
+#pragma unroll
+    for (int i = 0; i < kScanPerWave; ++i) {
+      if (live && t0 + i < t1) col[(size_t)(t0 + i) * radix] = run;
+      run += v[i];
+    }
   }
+  if (live && wave == 0) col[(size_t)n_tiles * radix] = carry;  // the digit's total
+}
+
+// sum of the four bytes of a word
+__device__ __forceinline__ int byte_sum(uint32_t c) {
+  return (int)((((c & 0x00ff00ffu) + ((c >> 8) & 0x00ff00ffu)) * 0x00010001u) >> 16);
 }
 
 // ---- radix pass: stable scatter ---------------------------------------------------------------------
+// A key's place = start of its digit (over all tiles) + keys of that digit in earlier tiles + in
+// earlier rounds of this tile + in earlier waves of its round + its rank among the wave's keys of
+// that digit (ballots, in lane order).  LDS is kept under 32 KB so that a workgroup fits on a CU
+// beside one of the matrix-product kernel.
 __global__ void __launch_bounds__(kSortBlock) k_radix_scatter(GroupBatch gb, int pass, const int32_t *status) {
   if (*status != 0) return;
   const GroupProblem &p = gb.p[blockIdx.y];
   if (pass >= p.passes) return;
   const int tile0 = blockIdx.x * kSortTile;
   if (tile0 >= p.n) return;
-  // cnt[round][wave][digit]: keys with that digit seen by that wave in that round
-  __shared__ uint16_t cnt[kSortItems * 4 * kMaxRadix];
+  __shared__ uint32_t wave_cnt[kSortItems * kMaxRadix];    // [round][digit]: one byte per wave, keys of that digit (<= 64)
+  __shared__ uint16_t round_off[kSortItems * kMaxRadix];   // [round][digit]: keys of that digit in earlier rounds (< 2048)
   __shared__ int digit_off[kMaxRadix];
   __shared__ int scan_smem[8];
+  static_assert(kSortBlock == 256, "one byte of wave_cnt per wave");
   const int radix = 1 << p.digit_bits, shift = pass * p.digit_bits;
   const int n_tiles = (p.n + kSortTile - 1) / kSortTile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-  for (int i = threadIdx.x; i < kSortItems * 4 * radix / 2; i += kSortBlock) reinterpret_cast<uint32_t *>(cnt)[i] = 0u;
+  for (int i = threadIdx.x; i < kSortItems * radix; i += kSortBlock) wave_cnt[i] = 0u;
   {
     // exclusive scan of the digit totals (radix <= 2 * kSortBlock: two adjacent digits per thread)
     const int d0 = 2 * threadIdx.x, d1 = d0 + 1;
@@ -136,6 +163,7 @@ __global__ void __launch_bounds__(kSortBlock) k_radix_scatter(GroupBatch gb, int
 
   const int32_t *keys_in = pass_keys(p, pass);
   const int32_t *vals_in = p.vals[pass & 1];
+  uint8_t *wave_cnt8 = reinterpret_cast<uint8_t *>(wave_cnt);
   int32_t key[kSortItems], val[kSortItems], rank[kSortItems];
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
@@ -151,28 +179,30 @@ __global__ void __launch_bounds__(kSortBlock) k_radix_scatter(GroupBatch gb, int
       peers &= bit ? m : ~m;
     }
     rank[i] = __popcll(peers & ((1ull << lane) - 1ull));
-    if (valid && rank[i] == 0) cnt[(i * 4 + wave) * radix + digit] = (uint16_t)__popcll(peers);
+    if (valid && rank[i] == 0) wave_cnt8[(i * radix + digit) * 4 + wave] = (uint8_t)__popcll(peers);
   }
   __syncthreads();
-  // exclusive scan over (round, wave) for every digit
+  // keys of a digit in the rounds before, for every round
   for (int d = threadIdx.x; d < radix; d += kSortBlock) {
     int run = 0;
 #pragma unroll
-    for (int rw = 0; rw < kSortItems * 4; ++rw) {
-      const int c = cnt[rw * radix + d];
-      cnt[rw * radix + d] = (uint16_t)run;
-      run += c;
+    for (int r = 0; r < kSortItems; ++r) {
+      round_off[r * radix + d] = (uint16_t)run;
+      const uint32_t c = wave_cnt[r * radix + d];
+      run += byte_sum(c);
     }
   }
   __syncthreads();
   int32_t *keys_out = p.keys[(pass + 1) & 1];
   int32_t *vals_out = p.vals[(pass + 1) & 1];
+  const uint32_t waves_before = wave == 0 ? 0u : (0xffffffffu >> (32 - 8 * wave));
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
     const int q = tile0 + i * kSortBlock + threadIdx.x;
     if (q < p.n) {
       const int digit = (key[i] >> shift) & (radix - 1);
-      const int pos = digit_off[digit] + cnt[(i * 4 + wave) * radix + digit] + rank[i];
+      const int pos = digit_off[digit] + round_off[i * radix + digit] +
+                      byte_sum(wave_cnt[i * radix + digit] & waves_before) + rank[i];
       keys_out[pos] = key[i];
       vals_out[pos] = val[i];
     }
