@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--expiry", type=int, default=None,
                     help="instead of the periodic full refresh: before every step, recompute (here: replace by "
                          "stand-in rows) the cached DFVs the batch asks for that are at least this many steps old")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="also run the timed steps with every kernel on one stream, one after another (the per-kernel "
+                         "pass always does): the whole command then launches each kernel alone, which is what a "
+                         "kernel-trace profile should see when its averages are compared with `kernels`")
     ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: write profiles/traffic.json from two rocprofv3 --pmc counter CSVs of this benchmark")
     return ap.parse_args()
@@ -247,6 +251,7 @@ def main():
         g.gear_fill_normal(raw, wl.n_images, R, wl.seed + 3, 3, 1.0)
         g.gear_fill_normal(wd, wl.dfv_dim, R, wl.seed + 4, 3, R ** -0.5)
         dense = g.DenseStandIn(st, raw, wd, max_rows=max(dense_rows, wl.max_nnz))
+    st.one_stream = args.one_stream
     it = 0
     for _ in range(W):
         one_step(it)
@@ -270,8 +275,11 @@ def main():
     loss = float(st.loss.item())
     refreshed_per_step = float(np.mean(refreshed)) if refreshed else None
 
-    # per-kernel durations: the same steps again with HIP events around every launch
+    # per-kernel durations: the same steps again with HIP events around every launch, all on one
+    # stream, so that a duration is that of the kernel alone (in the timed steps above, parts of a
+    # step run side by side on two streams and share the device)
     st.profile = g.GearProfile()
+    st.one_stream = True
     spans, work = {}, {}
     for _ in range(K):
         one_step(it)
@@ -283,6 +291,7 @@ def main():
         it += 1
     st.profile.close()
     st.profile = None
+    st.one_stream = args.one_stream
 
     # the workload's periodic full DFV refresh (new vectors stand in for a Dense-Part inference pass)
     refresh_ms, copy_gbs, dense_refresh_ms = 0.0, None, None
@@ -339,7 +348,8 @@ def main():
     roofline = {"kernel": dominant["name"], "bound": dominant["bound"], "achieved": dominant["achieved"],
                 "peak": dominant["peak"], "unit": dominant["unit"], "frac": dominant["frac"],
                 "avg_launch_ms": dominant["ms_per_step"] / dominant["launches_per_step"],
-                "traffic": recorded_traffic(dominant["name"])}
+                "traffic": recorded_traffic(dominant["name"]),
+                "measured": "kernel alone: per-launch HIP events, all launches on one stream"}
 
     out = {
         "metric": "page-views/sec per gear_step at 1 GPU", "value": value, "unit": "page-views/s",
@@ -353,7 +363,7 @@ def main():
                    "expired_rows_per_step": refreshed_per_step,
                    "loop_ms_per_step": loop_ms / K, "profiled_ms_per_step": sum(r["ms_per_step"] for r in kernels),
                    "step_ms_p10_p50_p90": [float(np.percentile(step_ms, q)) for q in (10, 50, 90)],
-                   "hbm_copy_GBs": copy_gbs},
+                   "hbm_copy_GBs": copy_gbs, "timed_steps_on_one_stream": bool(args.one_stream)},
         "loss": loss,
         "roofline": roofline,
         "kernels": kernels,

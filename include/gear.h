@@ -109,6 +109,10 @@ typedef struct gear_step_out {
    * the step is then bracketed by HIP events on the stream it is launched on (the caller's or the
    * helper stream); read them with gear_profile_span after synchronising the caller's stream. */
   void *profile;
+  /* Nonzero: every kernel of the step is launched on the caller's stream, one after another, and
+   * the helper stream is not used.  Same results; for timing each kernel alone, or for callers
+   * that want no second stream. */
+  int32_t one_stream;
 } gear_step_out;
 
 /* Bytes of scratch device memory gear_step needs for this configuration (0 on a bad config). */

@@ -63,7 +63,8 @@ class gear_step_out(C.Structure):
     _fields_ = [("loss", C.c_void_p), ("n_ready", C.c_void_p), ("ready_ids", C.c_void_p),
                 ("ready_grads", C.c_void_p), ("ready_cap", C.c_int32), ("status", C.c_void_p),
                 ("dbg_img_unique", C.c_void_p), ("dbg_img_segoff", C.c_void_p),
-                ("dbg_img_perm", C.c_void_p), ("dbg_n_img_unique", C.c_void_p), ("profile", C.c_void_p)]
+                ("dbg_img_perm", C.c_void_p), ("dbg_n_img_unique", C.c_void_p), ("profile", C.c_void_p),
+                ("one_stream", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -238,6 +239,7 @@ class GearState:
         self.ready_ids = torch.empty(max(self.ready_cap, 1), dtype=torch.int32, device=dev)
         self.ready_grads = torch.empty((max(self.ready_cap, 1), cfg.dfv_dim), dtype=torch.float32, device=dev)
         self.profile = None          # a GearProfile to time every launch of the next steps
+        self.one_stream = False      # True: the next steps launch every kernel on the current stream
         self.dbg = None
         if debug:
             n = cfg.max_nnz
@@ -251,7 +253,7 @@ class GearState:
         d = self.dbg or (None, None, None, None)
         return gear_step_out(_ptr(self.loss), _ptr(self.n_ready), _ptr(self.ready_ids), _ptr(self.ready_grads),
                              self.ready_cap, _ptr(self.status), _ptr(d[0]), _ptr(d[1]), _ptr(d[2]), _ptr(d[3]),
-                             self.profile.handle if self.profile is not None else None)
+                             self.profile.handle if self.profile is not None else None, 1 if self.one_stream else 0)
 
     def layer_params(self, layer: int):
         """Views of W_l [out x in] and b_l [out] inside mlp_params."""

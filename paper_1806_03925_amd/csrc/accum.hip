@@ -15,19 +15,18 @@
 namespace gear {
 namespace {
 
-// A thread owns kCols<GT> consecutive columns: 16 bytes of a dLoss/dx row (4 fp32 or 8 bf16 values).
+// A thread owns kCols<GT> consecutive columns: 16 bytes of a dLoss/dx row (4 fp32 or 8 bf16 values),
+// kept as loaded until they are added.
 template <typename GT> struct Cols;
 template <> struct Cols<float> {
   static constexpr int N = 4;
-  static __device__ __forceinline__ void load(const float *p, float (&v)[4]) {
-    const float4 t = *reinterpret_cast<const float4 *>(p);
-    v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+  static __device__ __forceinline__ void widen(const uint4 &t, float (&v)[4]) {
+    v[0] = __uint_as_float(t.x), v[1] = __uint_as_float(t.y), v[2] = __uint_as_float(t.z), v[3] = __uint_as_float(t.w);
   }
 };
 template <> struct Cols<bf16_t> {
   static constexpr int N = 8;
-  static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[8]) {
-    const uint4 t = *reinterpret_cast<const uint4 *>(p);
+  static __device__ __forceinline__ void widen(const uint4 &t, float (&v)[8]) {
     v[0] = __uint_as_float(t.x << 16), v[1] = __uint_as_float(t.x & 0xffff0000u);
     v[2] = __uint_as_float(t.y << 16), v[3] = __uint_as_float(t.y & 0xffff0000u);
     v[4] = __uint_as_float(t.z << 16), v[5] = __uint_as_float(t.z & 0xffff0000u);
@@ -68,20 +67,17 @@ __device__ __forceinline__ void add_rows(float (&acc)[Cols<GT>::N], const int32_
       view[i] = in ? row_view[q + i] : -1;
       scale[i] = in ? row_scale[q + i] : 0.0f;
     }
-    float v[8][N];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (view[i] >= 0) {
-        Cols<GT>::load(col + (size_t)view[i] * D, v[i]);
-      } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) v[i][k] = 0.0f;
-      }
-    }
+    uint4 raw[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
+      raw[i] = view[i] >= 0 ? *reinterpret_cast<const uint4 *>(col + (size_t)view[i] * D) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-      for (int k = 0; k < N; ++k) acc[k] += v[i][k] * scale[i];
+    for (int i = 0; i < 8; ++i) {
+      float v[N];
+      Cols<GT>::widen(raw[i], v);
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[k] += v[k] * scale[i];
+    }
   }
 }
 

@@ -383,30 +383,34 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   // stream gathers and runs the forward pass: operand copies of the weights (needed by the first
   // product), the grouping, the accumulation plan and the counter update.  The main stream waits for
   // it before the first kernel that changes caller state, so the status word is final by then.
-  SideLane *side = side_lane();
-  if (!side) return GEAR_ERR_HIP;
-  GEAR_HIP(hipEventRecord(side->fork, s));
-  GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+  const bool one_stream = out->one_stream != 0;
+  SideLane *side = one_stream ? nullptr : side_lane();
+  if (!one_stream && !side) return GEAR_ERR_HIP;
+  hipStream_t helper = one_stream ? s : side->stream;
+  if (side) {
+    GEAR_HIP(hipEventRecord(side->fork, s));
+    GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+  }
   {
-    hipStream_t s = side->stream;  // the launches of this block go to the helper stream
+    hipStream_t s = helper;  // the launches of this block go to the helper stream
     {
       Span span_(prof, "cast_weights", s);
       for (int l = 0; l < L; ++l)
         GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt,
                                      ws + lay.wc[l], ws + lay.wct[l], status, s));
     }
-    GEAR_HIP(hipEventRecord(side->cast, s));
+    if (side) GEAR_HIP(hipEventRecord(side->cast, s));
     GEAR_RUN("group_ids", launch_group(gb, status, s));
     GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap,
                                              out->n_ready, status, s));
     GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
   }
-  GEAR_HIP(hipEventRecord(side->join, side->stream));
+  if (side) GEAR_HIP(hipEventRecord(side->join, side->stream));
 
   // forward
   void *x = ws + lay.x;
   GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
-  GEAR_HIP(hipStreamWaitEvent(s, side->cast, 0));
+  if (side) GEAR_HIP(hipStreamWaitEvent(s, side->cast, 0));
   // A hidden layer below the last one also leaves the sign bitmap of its activations when both its
   // own product and the dgrad product that masks with it run in the kernel that knows bitmaps: the
   // backward pass then reads one bit per unit instead of the activation.
@@ -419,7 +423,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
                                      ws + lay.h[l], 0, nullptr, relu_bits[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
-  GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
+  if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
   GEAR_RUN("logit_loss_sgd",
            launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.w_off[L - 1],
                              t->mlp_params + lay.b_off[L - 1], t->mlp_params + lay.b_off[L - 2], b->label, B,
@@ -455,17 +459,24 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     }
   }
 
-  // SGD on the touched embedding rows (helper stream, beside the weight-gradient products) and the
-  // per-image gradient bookkeeping; both only need dLoss/dx
-  GEAR_HIP(hipEventRecord(side->fork, s));
-  GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+  // What only needs dLoss/dx goes to the helper stream: SGD on the touched embedding rows, then the
+  // per-image gradient bookkeeping.  Both are bound by memory traffic and run beside the
+  // weight-gradient products, which are not.  The bookkeeping comes second so that the products
+  // hold their CUs before its many small workgroups arrive: those fill what is left, whereas a
+  // product arriving later would wait for room among them.
+  if (side) {
+    GEAR_HIP(hipEventRecord(side->fork, s));
+    GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+  }
   {
-    hipStream_t s = side->stream;
+    hipStream_t s = helper;
     GEAR_RUN("embedding_update",
              launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
                                      (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
+    GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
+                                             out->ready_grads, status, s));
   }
-  GEAR_HIP(hipEventRecord(side->join, side->stream));
+  if (side) GEAR_HIP(hipEventRecord(side->join, side->stream));
   // SGD on the hidden layers' weights: split-K wgrad (logit layer and all biases are done above)
   for (int l = L - 2; l >= 0; --l) {
     const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
@@ -475,9 +486,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                              t->mlp_params + lay.w_off[l], opt, moments_at(mom_mlp, lay.w_off[l]),
                                              status, s));
   }
-
-  GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
-                                           out->ready_grads, status, s));
+  if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
   if (out->dbg_img_unique && b->nnz > 0)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_unique, gb.p[2].unique, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_img_segoff)
@@ -486,7 +495,6 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_perm, gb.p[2].perm, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_n_img_unique)
     GEAR_HIP(hipMemcpyAsync(out->dbg_n_img_unique, gb.p[2].n_unique, 4, hipMemcpyDeviceToDevice, s));
-  GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
   return GEAR_OK;
 }
 

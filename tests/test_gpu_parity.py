@@ -498,6 +498,27 @@ def test_same_step_twice_is_bit_identical():
         assert torch.equal(a, b)
 
 
+def test_one_stream_and_two_streams_give_the_same_bits():
+    """The step with every kernel on the caller's stream against the step that runs parts of itself
+    on the helper stream: same launches, same order of every sum, so every output bit agrees."""
+    wl = get_workload("bf16").scaled(n_users=100_000, n_urls=1 << 16, n_images=5_000, M=4)
+    outs = []
+    for one in (False, True):
+        cfg, st, _ = make_pair(wl, max_batch=3000)
+        st.one_stream = one
+        src = PageViewSource(wl)
+        for step in range(3):
+            g.gear_step(st, g.DeviceBatch.from_host(src.batch(step, batch=3000)), wl.M, 0.5)
+        torch.cuda.synchronize()
+        assert int(st.status.item()) == 0
+        n = int(st.n_ready.item())
+        assert n > 0
+        outs.append([t.clone() for t in (st.loss, st.ready_ids[:n], st.ready_grads[:n], st.grad_accum, st.counts,
+                                         st.user_emb, st.url_emb, st.mlp_params)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ edge cases
 def test_empty_views_duplicates_and_single_view():
     wl = get_workload("tiny").scaled(M=2)
