@@ -208,7 +208,7 @@ def main():
 
     K, W = args.steps, args.warmup
     src = PageViewSource(wl)
-    pool = min(W + 2 * K, 160)
+    pool = min(W + 3 * K, 160)
     host = [src.batch(i) for i in range(pool)]
     dev = [g.DeviceBatch.from_host(b) for b in host]
     lr = float(wl.lr)
@@ -259,21 +259,29 @@ def main():
         it += 1
     torch.cuda.synchronize()
     refreshed.clear()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
     t0 = time.perf_counter()
-    marks[0].record()
     for i in range(K):
         one_step(it)
-        marks[i + 1].record()      # between steps on the launch stream: costs no synchronisation
         it += 1
     torch.cuda.synchronize()
     loop_ms = (time.perf_counter() - t0) * 1e3
-    step_ms = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(K)])
     for i in range(it - K, it):
         model.step(host[i % pool])
     assert int(st.status.item()) == 0 and np.isfinite(float(st.loss.item()))
     loss = float(st.loss.item())
     refreshed_per_step = float(np.mean(refreshed)) if refreshed else None
+
+    # spread of the step time: the same again with an event between steps (each costs the launch
+    # stream a few microseconds, which is why the timed steps above carry none)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    marks[0].record()
+    for i in range(K):
+        one_step(it)
+        model.step(host[it % pool])
+        marks[i + 1].record()
+        it += 1
+    torch.cuda.synchronize()
+    step_ms = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(K)])
 
     # per-kernel durations: the same steps again with HIP events around every launch, all on one
     # stream, so that a duration is that of the kernel alone (in the timed steps above, parts of a
