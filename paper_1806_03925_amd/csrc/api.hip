@@ -170,6 +170,8 @@ bool make_layout(const gear_config &c, Layout *lay) {
   lay->row_view = take(&cur, NNZ * sizeof(int32_t));
   lay->row_scale = take(&cur, NNZ * sizeof(float));
   lay->n_units = take(&cur, sizeof(int32_t));
+  lay->expiry_marks = take(&cur, (size_t)expiry_words(c.n_images) * sizeof(uint32_t));
+  lay->expiry_tiles = take(&cur, (size_t)expiry_tiles(c.n_images) * sizeof(int32_t));
   lay->total = cur;
   return true;
 }
@@ -548,14 +550,8 @@ gear_status gear_expired_ids(const gear_config *cfg, const int32_t *image_ids, i
   hipStream_t s = (hipStream_t)stream;
   char *ws = (char *)workspace;
   GEAR_HIP(launch_fill_zero(status, sizeof(int32_t), s));
-  GroupBatch gb;
-  gb.count = 1;
-  // keys are sorted on the bits of a valid id; the filter checks the range before it indexes the stamps
-  gb.p[0] = make_problem(lay, ws, 2, image_ids, n, cfg->n_images);
-  gb.p[0].pos_seg = nullptr;
-  GEAR_HIP(launch_group(gb, status, s));
-  GEAR_HIP(launch_expired(gb.p[0], dfv_stamp, cfg->n_images, now, expiry, (int32_t *)(ws + lay.tile_units), expired_ids,
-                          n_expired, status, s));
+  GEAR_HIP(launch_expired(image_ids, n, dfv_stamp, cfg->n_images, now, expiry, (uint8_t *)(ws + lay.expiry_marks),
+                          (int32_t *)(ws + lay.expiry_tiles), expired_ids, n_expired, status, s));
   return GEAR_OK;
 }
 

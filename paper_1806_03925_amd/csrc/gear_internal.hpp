@@ -167,6 +167,7 @@ struct Layout {
     size_t keys[2], vals[2], block_hist, tile_heads, unique, segoff, pos_seg, n_unique;
   } g[kMaxProblems];
   size_t tile_units, tile_emits, units, row_view, row_scale, n_units;
+  size_t expiry_marks, expiry_tiles;  // gear_expired_ids: byte map over the images, marked bytes per tile
   size_t total;
 };
 
@@ -189,9 +190,13 @@ hipError_t launch_validate(const gear_config &cfg, const gear_batch &b, int32_t 
 
 hipError_t launch_group(const GroupBatch &gb, const int32_t *status, hipStream_t s);
 // distinct ids of a grouped list whose cache entry is older than `expiry`, ascending
-hipError_t launch_expired(const GroupProblem &img, const int32_t *stamp, int64_t n_images, int32_t now,
-                          int32_t expiry, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out, int32_t *status,
-                          hipStream_t s);
+// words (four images each) of the byte map over all images that the expiry filter marks, and tiles
+// of kSortTile words
+inline int64_t expiry_words(int64_t n_images) { return (n_images + 3) / 4; }
+inline int64_t expiry_tiles(int64_t n_images) { return (expiry_words(n_images) + kSortTile - 1) / kSortTile; }
+hipError_t launch_expired(const int32_t *image_ids, int n, const int32_t *stamp, int64_t n_images, int32_t now,
+                          int32_t expiry, uint8_t *marks, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out,
+                          int32_t *status, hipStream_t s);
 hipError_t launch_stamp(int32_t *stamp, int64_t n_images, const int32_t *ids, int64_t n, int32_t now, int32_t *status,
                         hipStream_t s);
 hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *occ_view,

@@ -383,8 +383,11 @@ __global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, Acc
 }
 
 // ---- expiry of cached inference results ------------------------------------------------------------
-// The distinct image ids of a batch (segment heads of the grouping) are filtered by age and
-// compacted in order: per-tile counts, then a scatter at the tile's offset.
+// Every occurrence whose cached row is old writes a 1 into its image's byte of a map over all images
+// (a plain store of the same value, whoever comes first; an atomic OR into a bitmap was tried and
+// spent 260 us on the thousands of occurrences of the most popular image, all aimed at one word);
+// the marked bytes are then counted per tile and written out in ascending order at the tile's
+// offset.  No sort is needed: the map is already in id order.
 __device__ __forceinline__ bool is_expired(const int32_t *__restrict__ stamp, int64_t n_images, int id, int32_t now,
                                            int32_t expiry, int32_t *status) {
   if (id < 0 || id >= n_images) {
@@ -394,48 +397,59 @@ __device__ __forceinline__ bool is_expired(const int32_t *__restrict__ stamp, in
   return (int64_t)now - (int64_t)stamp[id] >= (int64_t)expiry;
 }
 
-__global__ void __launch_bounds__(kSortBlock) k_expired_count(GroupProblem p, const int32_t *__restrict__ stamp,
-                                                              int64_t n_images, int32_t now, int32_t expiry,
-                                                              int32_t *__restrict__ tile_counts, int32_t *status) {
-  const int n_unique = *p.n_unique;
-  const int tile0 = blockIdx.x * kSortTile;
+__global__ void __launch_bounds__(256) k_expired_mark(const int32_t *__restrict__ ids, int n,
+                                                      const int32_t *__restrict__ stamp, int64_t n_images, int32_t now,
+                                                      int32_t expiry, uint8_t *__restrict__ marks, int32_t *status) {
+  for (int r = blockIdx.x * blockDim.x + threadIdx.x; r < n; r += gridDim.x * blockDim.x) {
+    const int id = ids[r];
+    if (is_expired(stamp, n_images, id, now, expiry, status)) marks[id] = 1;
+  }
+}
+
+// The map is read as words of four images; thread t of a tile owns the words tile0 + 8 t .. + 7, so a
+// scan keeps id order.  The map is padded with zeros to a whole number of words.
+__global__ void __launch_bounds__(kSortBlock) k_expired_count(const uint32_t *__restrict__ marks, int64_t n_words,
+                                                              int32_t *__restrict__ tile_counts) {
+  const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
   __shared__ int smem[8];
   int c = 0;
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
-    const int q = tile0 + threadIdx.x * kSortItems + i;
-    if (q < n_unique && is_expired(stamp, n_images, p.unique[q], now, expiry, status)) ++c;
+    const int64_t w = tile0 + threadIdx.x * kSortItems + i;
+    if (w < n_words) c += __popc(marks[w]);
   }
   int total;
   block_exclusive_scan(c, &total, smem);
   if (threadIdx.x == 0) tile_counts[blockIdx.x] = total;
 }
 
-__global__ void __launch_bounds__(kSortBlock) k_expired_scatter(GroupProblem p, const int32_t *__restrict__ stamp,
-                                                                int64_t n_images, int32_t now, int32_t expiry,
+__global__ void __launch_bounds__(kSortBlock) k_expired_scatter(const uint32_t *__restrict__ marks, int64_t n_words,
                                                                 const int32_t *__restrict__ tile_counts,
                                                                 int32_t *__restrict__ out_ids, int32_t *n_out,
-                                                                int32_t *status) {
-  const int n_unique = *p.n_unique;
-  const int tile0 = blockIdx.x * kSortTile;
+                                                                const int32_t *status) {
+  const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
   __shared__ int smem[8];
   const int base = sum_before(tile_counts, blockIdx.x, smem);
-  bool hit[kSortItems];
+  uint32_t word[kSortItems];
   int c = 0;
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
-    const int q = tile0 + threadIdx.x * kSortItems + i;
-    hit[i] = q < n_unique && is_expired(stamp, n_images, p.unique[q], now, expiry, status);
-    c += hit[i] ? 1 : 0;
+    const int64_t w = tile0 + threadIdx.x * kSortItems + i;
+    word[i] = w < n_words ? marks[w] : 0u;
+    c += __popc(word[i]);
   }
   int total;
   int at = base + block_exclusive_scan(c, &total, smem);
-  const bool bad = *status != 0;   // set by the count pass, which saw every id: the list is then empty
+  const bool bad = *status != 0;   // set by the marking pass, which saw every id: the list is then empty
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
-    const int q = tile0 + threadIdx.x * kSortItems + i;
-    if (hit[i] && !bad) out_ids[at] = p.unique[q];
-    at += hit[i] ? 1 : 0;
+    const int64_t w = tile0 + threadIdx.x * kSortItems + i;
+#pragma unroll
+    for (int byte = 0; byte < 4; ++byte)
+      if (word[i] & (1u << (8 * byte))) {
+        if (!bad) out_ids[at] = (int32_t)(w * 4 + byte);
+        ++at;
+      }
   }
   if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *n_out = bad ? 0 : base + total;
 }
@@ -454,14 +468,22 @@ __global__ void __launch_bounds__(256) k_stamp(int32_t *__restrict__ stamp, int6
 
 }  // namespace
 
-hipError_t launch_expired(const GroupProblem &img, const int32_t *stamp, int64_t n_images, int32_t now,
-                          int32_t expiry, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out, int32_t *status,
-                          hipStream_t s) {
-  int tiles = (img.n + kSortTile - 1) / kSortTile;
-  if (tiles < 1) tiles = 1;
-  hipLaunchKernelGGL(k_expired_count, dim3(tiles), dim3(kSortBlock), 0, s, img, stamp, n_images, now, expiry,
-                     tile_counts, status);
-  hipLaunchKernelGGL(k_expired_scatter, dim3(tiles), dim3(kSortBlock), 0, s, img, stamp, n_images, now, expiry,
+hipError_t launch_expired(const int32_t *image_ids, int n, const int32_t *stamp, int64_t n_images, int32_t now,
+                          int32_t expiry, uint8_t *marks, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out,
+                          int32_t *status, hipStream_t s) {
+  const int64_t n_words = expiry_words(n_images);
+  hipError_t e = launch_fill_zero(marks, (size_t)n_words * sizeof(uint32_t), s);
+  if (e != hipSuccess) return e;
+  if (n > 0) {
+    int blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_expired_mark, dim3(blocks), dim3(256), 0, s, image_ids, n, stamp, n_images, now, expiry, marks,
+                       status);
+  }
+  const int tiles = (int)expiry_tiles(n_images);
+  hipLaunchKernelGGL(k_expired_count, dim3(tiles), dim3(kSortBlock), 0, s, (const uint32_t *)marks, n_words,
+                     tile_counts);
+  hipLaunchKernelGGL(k_expired_scatter, dim3(tiles), dim3(kSortBlock), 0, s, (const uint32_t *)marks, n_words,
                      tile_counts, out_ids, n_out, status);
   return hipGetLastError();
 }

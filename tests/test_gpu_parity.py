@@ -296,6 +296,25 @@ def test_expired_ids_and_stamps_match_oracle():
     assert int((stamp != 77).sum().item()) == 0
 
 
+def test_expired_ids_over_several_tiles_of_images():
+    """The same list against its definition (ascending distinct ids that are old enough) with an image
+    count that spans several tiles of the filter's bitmap and ends inside a word."""
+    wl = get_workload("small").scaled(n_images=200_003, n_users=1000, n_urls=1024)
+    cfg, st, _ = make_pair(wl)
+    rng = np.random.default_rng(11)
+    stamp_h = rng.integers(0, 10, wl.n_images).astype(np.int32)
+    stamp = torch.from_numpy(stamp_h).cuda()
+    for n, now, expiry in [(wl.max_nnz, 10, 4), (wl.max_nnz, 10, 0), (777, 12, 11), (5, 3, 20)]:
+        ids_h = rng.integers(0, wl.n_images, n).astype(np.int32)
+        ids_h[: min(n, 3)] = [wl.n_images - 1, 0, wl.n_images - 1][: min(n, 3)]      # both ends, one twice
+        out, n_out = g.gear_expired_ids(st, torch.from_numpy(ids_h).cuda(), stamp, now, expiry)
+        torch.cuda.synchronize()
+        u = np.unique(ids_h)
+        want = u[(now - stamp_h[u].astype(np.int64)) >= expiry]
+        assert int(st.status.item()) == 0 and int(n_out.item()) == len(want), (n, now, expiry)
+        assert np.array_equal(out[: len(want)].cpu().numpy(), want.astype(np.int32))
+
+
 @pytest.mark.parametrize("name,batch,eps", [("tiny", 512, 1e-4), ("small", 1200, 1e-4), ("bf16", 1500, 1e-4),
                                             ("small", 1200, 1e-8)])
 def test_adam_steps_free_running(name, batch, eps):
