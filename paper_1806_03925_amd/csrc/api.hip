@@ -366,7 +366,6 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   GEAR_RUN("begin", launch_begin(status, out->n_ready, out->loss, s));
   if (B == 0) return GEAR_OK;
   int32_t *occ_view = (int32_t *)(ws + lay.occ_view);
-  GEAR_RUN("validate", launch_validate(*cfg, *b, occ_view, status, s));
 
   // grouping of the three id lists and the plan of the per-image accumulation
   GroupBatch gb;
@@ -382,9 +381,11 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   plan.row_scale = (float *)(ws + lay.row_scale);
   plan.n_units = (int32_t *)(ws + lay.n_units);
   // What depends only on ids, counters and pre-step parameters runs on the helper stream while the main
-  // stream gathers and runs the forward pass: operand copies of the weights (needed by the first
-  // product), the grouping, the accumulation plan and the counter update.  The main stream waits for
-  // it before the first kernel that changes caller state, so the status word is final by then.
+  // stream gathers and runs the forward pass: the check of the ids, operand copies of the weights
+  // (needed by the first product), the grouping, the accumulation plan and the counter update.  The
+  // main stream waits for it before the first kernel that changes caller state, so the status word
+  // is final by then; until then its kernels write the workspace only, and the gather clamps what it
+  // uses as an index.
   const bool one_stream = out->one_stream != 0;
   SideLane *side = one_stream ? nullptr : side_lane();
   if (!one_stream && !side) return GEAR_ERR_HIP;
@@ -395,6 +396,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   }
   {
     hipStream_t s = helper;  // the launches of this block go to the helper stream
+    GEAR_RUN("validate", launch_validate(*cfg, *b, occ_view, status, s));
     {
       Span span_(prof, "cast_weights", s);
       for (int l = 0; l < L; ++l)
@@ -411,7 +413,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
 
   // forward
   void *x = ws + lay.x;
-  GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, status, s));
+  GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, s));
   if (side) GEAR_HIP(hipStreamWaitEvent(s, side->cast, 0));
   // A hidden layer below the last one also leaves the sign bitmap of its activations when both its
   // own product and the dgrad product that masks with it run in the kernel that knows bitmaps: the

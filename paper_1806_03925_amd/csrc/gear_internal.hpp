@@ -204,7 +204,7 @@ hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, con
                              int32_t *n_ready, int32_t *status, hipStream_t s);
 
 hipError_t launch_gather_pool(const gear_config &cfg, const gear_batch &b, const gear_tables &t,
-                              const void *dfv_cache, void *x, const int32_t *status, hipStream_t s);
+                              const void *dfv_cache, void *x, hipStream_t s);
 
 hipError_t launch_cast_weights(const float *w, int rows, int cols, int dtype, void *wc, void *wct,
                                const int32_t *status, hipStream_t s);
