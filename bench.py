@@ -50,8 +50,10 @@ def parse_args():
                     help="also run the timed steps with every kernel on one stream, one after another (the per-kernel "
                          "pass always does): the whole command then launches each kernel alone, which is what a "
                          "kernel-trace profile should see when its averages are compared with `kernels`")
-    ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
-                    help="no GPU work: write profiles/traffic.json from two rocprofv3 --pmc counter CSVs of this benchmark")
+    ap.add_argument("--record-traffic", nargs="+", metavar="CSV",
+                    help="no GPU work: FETCH_CSV WRITE_CSV [BENCH_LOG]: write profiles/traffic.json and the summary "
+                         "profiles/gear_step_large_hbm_traffic.txt from two rocprofv3 --pmc counter CSVs of this benchmark "
+                         "(BENCH_LOG: what one of those runs printed, for the algorithmic bytes of the same steps)")
     return ap.parse_args()
 
 
@@ -121,7 +123,45 @@ def recorded_traffic(span):
     return rec["bytes"]
 
 
-def record_traffic(fetch_csv, write_csv, refresh_bytes):
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "gear_step_large_hbm_traffic.txt")
+
+
+def write_traffic_summary(rec, refresh_bytes, bench_log=None):
+    """The counters of profiles/traffic.json as a table, with the commands that produce them."""
+    k, cal = rec["kernels"], rec["calibration"]
+    run = "python3 bench.py --steps 3 --warmup 1 --cpu-sample-views 0 --one-stream"
+    lines = [
+        '# HBM traffic per launch of the timed kernels of gear_step, workload "large" (B=65536), from rocprofv3 counters',
+        "# commands (one counter per run; run from the repository root after `cd /tmp && export TMPDIR=/tmp`):",
+        f"#   rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pmc_fetch -o f --output-format csv -- {run} > gpurun_out/pmc_fetch.log",
+        f"#   rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pmc_write -o w --output-format csv -- {run} > gpurun_out/pmc_write.log",
+        "#   python3 bench.py --record-traffic gpurun_out/pmc_fetch/f_counter_collection.csv "
+        "gpurun_out/pmc_write/w_counter_collection.csv gpurun_out/pmc_fetch.log",
+        f"# calibration: the full DFV refresh (k_refresh) copies {refresh_bytes:,} bytes in and out in the same runs;",
+        f"#   FETCH_SIZE reads {refresh_bytes / cal['fetch_bytes_per_count']:.0f} for it -> {cal['fetch_bytes_per_count']:.1f} "
+        "bytes per count (the counter's KiB unit sees half of the 128-byte reads)",
+        f"#   WRITE_SIZE reads {refresh_bytes / cal['write_bytes_per_count']:.0f} for it -> {cal['write_bytes_per_count']:.1f} "
+        "bytes per count",
+        f"# averages over {k['accumulate']['launches']} launches (the first steps after initialisation, every kernel alone "
+        "on one stream); the machine-readable copy is profiles/traffic.json",
+        f"{'launch':16s} {'fetch_MB':>10s} {'write_MB':>10s} {'total_MB':>10s}",
+    ]
+    for n, v in sorted(k.items(), key=lambda kv: -kv[1]["bytes"]):
+        lines.append(f"{n:16s} {v['fetch_bytes'] / 1e6:10.1f} {v['write_bytes'] / 1e6:10.1f} {v['bytes'] / 1e6:10.1f}")
+    if bench_log:
+        line = [l for l in open(bench_log) if l.startswith("{")][-1]
+        alg = {r["name"]: r.get("algorithmic_per_launch") for r in json.loads(line)["kernels"]}
+        lines.append("# algorithmic bytes per launch in the same steps (this benchmark's work model): "
+                     f"accumulate {alg['accumulate'] / 1e6:.1f} MB, gather_pool {alg['gather_pool'] / 1e6:.1f} MB")
+        lines.append("# (accumulate's grows with the step number, as more images carry a partial sum that has to be read: "
+                     "about 850 MB around step 100)")
+    lines += ["# the excess is re-reads of dLoss/dx rows (accumulate: one row per occurrence, 4.5 per view) and of cached "
+              "DFV rows (gather) that miss in L2.",
+              "# dgrad_gemm_l1 reads the 8 MB sign bitmap of the first hidden layer instead of its 134 MB of activations."]
+    open(TRAFFIC_SUMMARY, "w").write("\n".join(lines) + "\n")
+
+
+def record_traffic(fetch_csv, write_csv, bench_log=None, refresh_bytes=0):
     """Turn two `rocprofv3 --pmc` runs of this benchmark (FETCH_SIZE, then WRITE_SIZE; counter CSVs) into
     profiles/traffic.json.  Each counter is scaled by what it reads for the full DFV refresh, a plain
     copy of `refresh_bytes` in and out."""
@@ -158,6 +198,7 @@ def record_traffic(fetch_csv, write_csv, refresh_bytes):
         rec["bytes"] = rec["fetch_bytes"] + rec["write_bytes"]
         out["kernels"][span] = rec
     json.dump(out, open(TRAFFIC_FILE, "w"), indent=1, sort_keys=True)
+    write_traffic_summary(out, refresh_bytes, bench_log)
     print(json.dumps(out, indent=1, sort_keys=True))
 
 
@@ -192,6 +233,8 @@ def main():
 
     wl = get_workload(args.workload)
     if args.record_traffic:
+        if len(args.record_traffic) not in (2, 3):
+            sys.exit("--record-traffic takes FETCH_CSV WRITE_CSV [BENCH_LOG]")
         record_traffic(*args.record_traffic, refresh_bytes=wl.n_images * wl.dfv_dim * BYTES[wl.dfv_dtype])
         return
 
