@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--expiry", type=int, default=None,
                     help="instead of the periodic full refresh: before every step, recompute (here: replace by "
                          "stand-in rows) the cached DFVs the batch asks for that are at least this many steps old")
+    ap.add_argument("--host-counts", action="store_true",
+                    help="with --expiry / --dense-raw-dim: read the number of expired rows / of emissions back to the host "
+                         "every step instead of leaving it on the device")
     ap.add_argument("--one-stream", action="store_true",
                     help="also run the timed steps with every kernel on one stream, one after another (the per-kernel "
                          "pass always does): the whole command then launches each kernel alone, which is what a "
@@ -272,18 +275,26 @@ def main():
     def one_step(i):
         if expiry is not None:
             ids, n_dev = g.gear_expired_ids(st, dev[i % pool].img_id, stamp, i, expiry)
-            n = int(n_dev.item())                      # the caller has to know how many rows to recompute
-            refreshed.append(n)
-            if n:
-                g.gear_refresh_dfv(st, ids[:n], fresh_pool[:n])
-                g.gear_stamp_dfv(st, stamp, ids[:n], i)
+            if args.host_counts:
+                n = int(n_dev.item())                  # a caller that has to know how many rows to recompute
+                refreshed.append(n)
+                if n:
+                    g.gear_refresh_dfv(st, ids[:n], fresh_pool[:n])
+                    g.gear_stamp_dfv(st, stamp, ids[:n], i)
+            else:                                      # the count stays on the device, the host runs ahead
+                refreshed.append(n_dev)
+                g.gear_refresh_dfv_n(st, ids, fresh_pool, n_dev)
+                g.gear_stamp_dfv_n(st, stamp, ids, n_dev, i)
         if adam is None:
             g.gear_step(st, dev[i % pool], wl.M, lr)
         else:
             g.gear_step_adam(st, dev[i % pool], wl.M, lr, adam)
         if dense is not None:
-            n_ready = int(st.n_ready.item())           # the Dense Part's caller has to know how many arrived
-            dense.backward(st.ready_ids, st.ready_grads, n_ready, lr)
+            if args.host_counts:
+                n_ready = int(st.n_ready.item())       # a caller that has to know how many arrived
+                dense.backward(st.ready_ids, st.ready_grads, n_ready, lr)
+            else:
+                dense.backward_n(st.ready_ids, st.ready_grads, st.n_ready, lr)
 
     adam = g.AdamMoments(st) if args.optimizer == "adam" else None
     dense, dense_rows = None, 1 << 18
@@ -312,7 +323,7 @@ def main():
         model.step(host[i % pool])
     assert int(st.status.item()) == 0 and np.isfinite(float(st.loss.item()))
     loss = float(st.loss.item())
-    refreshed_per_step = float(np.mean(refreshed)) if refreshed else None
+    refreshed_per_step = float(np.mean([int(r) for r in refreshed])) if refreshed else None   # device words are read here
 
     # spread of the step time: the same again with an event between steps (each costs the launch
     # stream a few microseconds, which is why the timed steps above carry none)

@@ -215,6 +215,17 @@ gear_status gear_expired_ids(const gear_config *cfg, const int32_t *image_ids, i
 gear_status gear_stamp_dfv(const gear_config *cfg, int32_t *dfv_stamp, const int32_t *image_ids, int64_t n,
                            int32_t now, int32_t *status, void *stream);
 
+/* gear_refresh_dfv and gear_stamp_dfv for a list whose length is only known on the device (the
+ * output of gear_expired_ids, say): rows r < *n_rows are used, where n_rows is a device word read
+ * when the kernels run, 0 <= *n_rows <= max_rows (a larger value is cut to max_rows); image_ids and
+ * new_dfv hold max_rows entries.  The host need not read the count and can keep enqueuing.
+ * Otherwise as the calls above (image_ids must be given). */
+gear_status gear_refresh_dfv_n(const gear_config *cfg, void *dfv_cache, const int32_t *image_ids,
+                               const void *new_dfv, const int32_t *n_rows, int64_t max_rows, int32_t *status,
+                               void *stream);
+gear_status gear_stamp_dfv_n(const gear_config *cfg, int32_t *dfv_stamp, const int32_t *image_ids,
+                             const int32_t *n_rows, int64_t max_rows, int32_t now, int32_t *status, void *stream);
+
 /* A stand-in Dense Part, so that the loop of the method can be closed on one device: a linear map
  * DFV[i] = Wd raw[i] from fixed per-image features raw [n_images x raw_dim] (f32, device) with
  * weights Wd [dfv_dim x raw_dim] (f32, device).  Not the paper's CNN: the smallest model that has
@@ -246,6 +257,14 @@ gear_status gear_dense_backward(const gear_dense_config *cfg, const float *raw, 
                                 const int32_t *ready_ids, const float *ready_grads, int32_t n_ready,
                                 float lr, void *workspace, size_t workspace_bytes, int32_t *status,
                                 void *stream);
+
+/* The same with the number of emissions read from the device word n_ready when the kernels run
+ * (a step's gear_step_out.n_ready; at most max_rows, which ready_ids and ready_grads must hold): the
+ * host need not read it back.  The sum is split into a fixed number of ranges over *n_ready. */
+gear_status gear_dense_backward_n(const gear_dense_config *cfg, const float *raw, float *wd,
+                                  const int32_t *ready_ids, const float *ready_grads, const int32_t *n_ready,
+                                  float lr, void *workspace, size_t workspace_bytes, int32_t *status,
+                                  void *stream);
 
 /* Sort-by-key grouping used for the embedding updates and the per-image accumulation, exposed
  * for tests: keys [n] in [0, key_range) -> distinct keys ascending (unique [n]), segment offsets

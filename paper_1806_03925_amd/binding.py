@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
     "gear_fill_normal", "gear_init_tables", "gear_step", "gear_step_adam", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
-    "gear_dense_workspace_bytes", "gear_dense_infer", "gear_dense_backward", "gear_group_ids",
+    "gear_refresh_dfv_n", "gear_stamp_dfv_n",
+    "gear_dense_workspace_bytes", "gear_dense_infer", "gear_dense_backward", "gear_dense_backward_n", "gear_group_ids",
     "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
     "gear_status_string",
 )
@@ -110,6 +111,15 @@ def _load() -> C.CDLL:
     lib.gear_dense_backward.restype = C.c_int
     lib.gear_dense_backward.argtypes = [dcp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float,
                                         C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.gear_dense_backward_n.restype = C.c_int
+    lib.gear_dense_backward_n.argtypes = [dcp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
+                                          C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.gear_refresh_dfv_n.restype = C.c_int
+    lib.gear_refresh_dfv_n.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                       C.c_void_p]
+    lib.gear_stamp_dfv_n.restype = C.c_int
+    lib.gear_stamp_dfv_n.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
+                                     C.c_void_p]
     lib.gear_group_ids.restype = C.c_int
     lib.gear_group_ids.argtypes = [cfgp, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -370,6 +380,19 @@ def gear_refresh_dfv(state: GearState, image_ids: Optional[torch.Tensor], new_df
                                 _ptr(state.status), _stream()), "gear_refresh_dfv")
 
 
+def gear_refresh_dfv_n(state: GearState, image_ids: torch.Tensor, new_dfv: torch.Tensor, n_rows: torch.Tensor) -> None:
+    """Rows r < n_rows[0] (a device word) of image_ids / new_dfv; the host does not read the count."""
+    max_rows = min(int(image_ids.numel()), int(new_dfv.shape[0]))
+    _check(lib.gear_refresh_dfv_n(C.byref(state.cfg), _ptr(state.dfv_cache), _ptr(image_ids), _ptr(new_dfv), _ptr(n_rows),
+                                  max_rows, _ptr(state.status), _stream()), "gear_refresh_dfv_n")
+
+
+def gear_stamp_dfv_n(state: GearState, dfv_stamp: torch.Tensor, image_ids: torch.Tensor, n_rows: torch.Tensor,
+                     now: int) -> None:
+    _check(lib.gear_stamp_dfv_n(C.byref(state.cfg), _ptr(dfv_stamp), _ptr(image_ids), _ptr(n_rows),
+                                int(image_ids.numel()), int(now), _ptr(state.status), _stream()), "gear_stamp_dfv_n")
+
+
 def gear_expired_ids(state: GearState, image_ids: torch.Tensor, dfv_stamp: torch.Tensor, now: int, expiry: int):
     """Returns (ids buffer [n], n_expired [1]), both on the device; the first n_expired ids are valid."""
     n = int(image_ids.numel())
@@ -416,6 +439,13 @@ class DenseStandIn:
         _check(lib.gear_dense_backward(C.byref(self.cfg), _ptr(self.raw), _ptr(self.wd), _ptr(ready_ids),
                                        _ptr(ready_grads), int(n_ready), lr, _ptr(self.workspace),
                                        self.workspace.numel(), _ptr(self.status), _stream()), "gear_dense_backward")
+
+    def backward_n(self, ready_ids: torch.Tensor, ready_grads: torch.Tensor, n_ready: torch.Tensor, lr: float) -> None:
+        """The same with the number of emissions left on the device (a step's n_ready word)."""
+        assert ready_ids.numel() >= self.cfg.max_rows and ready_grads.shape[0] >= self.cfg.max_rows
+        _check(lib.gear_dense_backward_n(C.byref(self.cfg), _ptr(self.raw), _ptr(self.wd), _ptr(ready_ids),
+                                         _ptr(ready_grads), _ptr(n_ready), lr, _ptr(self.workspace),
+                                         self.workspace.numel(), _ptr(self.status), _stream()), "gear_dense_backward_n")
 
 
 def gear_group_ids(state: GearState, keys: torch.Tensor, key_range: int):

@@ -158,7 +158,8 @@ __global__ void __launch_bounds__(256) k_count_update(GroupProblem img, int32_t 
 // dfv_cache[ids[r]] = rows[r]; one wavefront per row, 16-byte pieces
 __global__ void __launch_bounds__(256) k_refresh(uint4 *__restrict__ cache, int64_t n_images, int vec_per_row,
                                                  const int32_t *__restrict__ ids, const uint4 *__restrict__ rows,
-                                                 int64_t n, int32_t *status) {
+                                                 int64_t n, int32_t *status, const int32_t *__restrict__ n_dev) {
+  if (n_dev) n = min((int64_t)max(*n_dev, 0), n);  // the row count is only known on the device
   const int lane = threadIdx.x & 63;
   const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
   for (int64_t r = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave; r < n; r += waves) {
@@ -200,13 +201,13 @@ hipError_t launch_count_update(const GroupProblem &img, int32_t *counts, const i
 }
 
 hipError_t launch_refresh(int dtype, void *dfv_cache, int64_t n_images, int dim, const int32_t *ids,
-                          const void *rows, int64_t n, int32_t *status, hipStream_t s) {
+                          const void *rows, int64_t n, int32_t *status, hipStream_t s, const int32_t *n_dev) {
   if (n <= 0) return hipSuccess;
   const int vec_per_row = (int)((size_t)dim * dtype_bytes(dtype) / 16);
   int64_t want = (n + 3) / 4;
   const int blocks = (int)(want < 16384 ? want : 16384);
   hipLaunchKernelGGL(k_refresh, dim3(blocks), dim3(256), 0, s, (uint4 *)dfv_cache, n_images, vec_per_row, ids,
-                     (const uint4 *)rows, n, status);
+                     (const uint4 *)rows, n, status, n_dev);
   return hipGetLastError();
 }
 

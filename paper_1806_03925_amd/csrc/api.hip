@@ -512,6 +512,23 @@ gear_status gear_refresh_dfv(const gear_config *cfg, void *dfv_cache, const int3
   return GEAR_OK;
 }
 
+gear_status gear_refresh_dfv_n(const gear_config *cfg, void *dfv_cache, const int32_t *image_ids, const void *new_dfv,
+                               const int32_t *n_rows, int64_t max_rows, int32_t *status, void *stream) {
+  if (!cfg || !config_ok(*cfg) || !dfv_cache || !image_ids || !n_rows || max_rows < 0 || (max_rows > 0 && !new_dfv))
+    return GEAR_ERR_INVALID;
+  if (!aligned16(dfv_cache) || !aligned16(new_dfv)) return GEAR_ERR_INVALID;
+  GEAR_HIP(launch_refresh(cfg->dfv_dtype, dfv_cache, cfg->n_images, cfg->dfv_dim, image_ids, new_dfv, max_rows, status,
+                          (hipStream_t)stream, n_rows));
+  return GEAR_OK;
+}
+
+gear_status gear_stamp_dfv_n(const gear_config *cfg, int32_t *dfv_stamp, const int32_t *image_ids, const int32_t *n_rows,
+                             int64_t max_rows, int32_t now, int32_t *status, void *stream) {
+  if (!cfg || !config_ok(*cfg) || !dfv_stamp || !image_ids || !n_rows || max_rows < 0) return GEAR_ERR_INVALID;
+  GEAR_HIP(launch_stamp(dfv_stamp, cfg->n_images, image_ids, max_rows, now, status, (hipStream_t)stream, n_rows));
+  return GEAR_OK;
+}
+
 gear_status gear_group_ids(const gear_config *cfg, const int32_t *keys, int32_t n, int64_t key_range, void *workspace,
                            size_t workspace_bytes, int32_t *unique, int32_t *segoff, int32_t *perm, int32_t *n_unique,
                            void *stream) {

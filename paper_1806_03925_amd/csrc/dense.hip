@@ -16,7 +16,8 @@ namespace {
 // out[r] = raw[ids[r]] (ids == NULL: raw[r]); one wavefront per row, 16-byte pieces
 __global__ void __launch_bounds__(256) k_gather_raw(const float4 *__restrict__ raw, int64_t n_images, int vec_per_row,
                                                     const int32_t *__restrict__ ids, int n, float4 *__restrict__ out,
-                                                    int32_t *status) {
+                                                    int32_t *status, const int32_t *__restrict__ n_dev) {
+  if (n_dev) n = min(max(*n_dev, 0), n);  // the row count is only known on the device
   const int lane = threadIdx.x & 63;
   const int waves = gridDim.x * (blockDim.x / kWave);
   for (int r = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave; r < n; r += waves) {
@@ -72,11 +73,11 @@ DenseLayout dense_layout(const gear_dense_config &c) {
   } while (0)
 
 hipError_t gather_raw(const gear_dense_config &c, const float *raw, const int32_t *ids, int n, float *out,
-                      int32_t *status, hipStream_t s) {
+                      int32_t *status, hipStream_t s, const int32_t *n_dev = nullptr) {
   int blocks = (n + 3) / 4;
   if (blocks > 8192) blocks = 8192;
   hipLaunchKernelGGL(k_gather_raw, dim3(blocks), dim3(256), 0, s, (const float4 *)raw, c.n_images, c.raw_dim / 4, ids, n,
-                     (float4 *)out, status);
+                     (float4 *)out, status, n_dev);
   return hipGetLastError();
 }
 
@@ -121,10 +122,11 @@ extern "C" gear_status gear_dense_infer(const gear_dense_config *cfg, const floa
   return GEAR_OK;
 }
 
-extern "C" gear_status gear_dense_backward(const gear_dense_config *cfg, const float *raw, float *wd,
-                                           const int32_t *ready_ids, const float *ready_grads, int32_t n_ready,
-                                           float lr, void *workspace, size_t workspace_bytes, int32_t *status,
-                                           void *stream) {
+namespace {
+// n_dev == NULL: n_ready emissions; otherwise up to n_ready, the real number read on the device
+gear_status dense_backward(const gear_dense_config *cfg, const float *raw, float *wd, const int32_t *ready_ids,
+                           const float *ready_grads, int32_t n_ready, const int32_t *n_dev, float lr, void *workspace,
+                           size_t workspace_bytes, int32_t *status, void *stream) {
   if (!cfg || !dense_ok(*cfg) || !raw || !wd || !workspace || !status || n_ready < 0 || n_ready > cfg->max_rows ||
       !std::isfinite(lr))
     return GEAR_ERR_INVALID;
@@ -138,15 +140,33 @@ extern "C" gear_status gear_dense_backward(const gear_dense_config *cfg, const f
   if (n_ready == 0) return GEAR_OK;
   char *ws = (char *)workspace;
   float *rows = (float *)(ws + lay.rows), *partial = (float *)(ws + lay.partial);
-  DENSE_HIP(gather_raw(*cfg, raw, ready_ids, n_ready, rows, status, s));
+  DENSE_HIP(gather_raw(*cfg, raw, ready_ids, n_ready, rows, status, s, n_dev));
   // dWd [D x r] = ready_grads [n x D]^T * rows [n x r], split over the emissions in a fixed shape; an id out
   // of range leaves the status word set and the weights untouched (both kernels below then stay idle)
-  int splits = (n_ready + 255) / 256;
+  int splits = n_dev ? lay.splits : (n_ready + 255) / 256;
   if (splits > lay.splits) splits = lay.splits;
   DENSE_HIP(launch_gemm_tn_splitk(GEAR_F32, ready_grads, rows, cfg->dfv_dim, cfg->raw_dim, n_ready, splits, partial,
-                                  status, s));
+                                  status, s, n_dev));
   const Optim sgd = {lr, 0.0f, 0.0f, 0.0f, 1.0f, 0};
   const Moments none = {nullptr, nullptr};
   DENSE_HIP(launch_splitk_sgd(partial, splits, (int64_t)cfg->dfv_dim * cfg->raw_dim, wd, sgd, none, status, s));
   return GEAR_OK;
+}
+}  // namespace
+
+extern "C" gear_status gear_dense_backward(const gear_dense_config *cfg, const float *raw, float *wd,
+                                           const int32_t *ready_ids, const float *ready_grads, int32_t n_ready,
+                                           float lr, void *workspace, size_t workspace_bytes, int32_t *status,
+                                           void *stream) {
+  return dense_backward(cfg, raw, wd, ready_ids, ready_grads, n_ready, nullptr, lr, workspace, workspace_bytes, status,
+                        stream);
+}
+
+extern "C" gear_status gear_dense_backward_n(const gear_dense_config *cfg, const float *raw, float *wd,
+                                             const int32_t *ready_ids, const float *ready_grads,
+                                             const int32_t *n_ready, float lr, void *workspace, size_t workspace_bytes,
+                                             int32_t *status, void *stream) {
+  if (!cfg || !n_ready) return GEAR_ERR_INVALID;
+  return dense_backward(cfg, raw, wd, ready_ids, ready_grads, cfg->max_rows, n_ready, lr, workspace, workspace_bytes,
+                        status, stream);
 }

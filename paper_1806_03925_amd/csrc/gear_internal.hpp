@@ -198,7 +198,7 @@ hipError_t launch_expired(const int32_t *image_ids, int n, const int32_t *stamp,
                           int32_t expiry, uint8_t *marks, int32_t *tile_counts, int32_t *out_ids, int32_t *n_out,
                           int32_t *status, hipStream_t s);
 hipError_t launch_stamp(int32_t *stamp, int64_t n_images, const int32_t *ids, int64_t n, int32_t now, int32_t *status,
-                        hipStream_t s);
+                        hipStream_t s, const int32_t *n_dev = nullptr);
 hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, const int32_t *occ_view,
                              const int32_t *img_off, const int32_t *counts, int32_t M, int32_t ready_cap,
                              int32_t *n_ready, int32_t *status, hipStream_t s);
@@ -228,8 +228,10 @@ bool gemm_nt_has_bits(int dtype, int K);
 hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, const Optim &opt, const Moments &mom,
                               const int32_t *status, hipStream_t s);
 // partial[z][M x N] = sum over the z-th K range of A[K x M]^T * B[K x N] (operands M-/N-contiguous).
+// k_dev (may be NULL): device word holding the real contraction length, at most K; the split into
+// `splits` ranges is then made on the device.
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
-                                 float *partial, const int32_t *status, hipStream_t s);
+                                 float *partial, const int32_t *status, hipStream_t s, const int32_t *k_dev = nullptr);
 int gemm_splitk_for(int M, int N, int K);  // wgrad split count for a [M x N] result contracted over K
 hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, const Optim &opt,
                              const Moments &mom, const int32_t *status, hipStream_t s);
@@ -255,7 +257,8 @@ hipError_t launch_accumulate(const gear_config &cfg, const GroupProblem &img, co
                              float *ready_grads, const int32_t *status, hipStream_t s);
 hipError_t launch_count_update(const GroupProblem &img, int32_t *counts, const int32_t *status, hipStream_t s);
 
+// n_dev (may be NULL): device word holding the real row count, at most n
 hipError_t launch_refresh(int dtype, void *dfv_cache, int64_t n_images, int dim, const int32_t *ids,
-                          const void *rows, int64_t n, int32_t *status, hipStream_t s);
+                          const void *rows, int64_t n, int32_t *status, hipStream_t s, const int32_t *n_dev = nullptr);
 
 }  // namespace gear

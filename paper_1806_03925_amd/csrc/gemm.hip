@@ -885,9 +885,16 @@ k_gemm_nt(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
 template <typename T>
 __global__ void __launch_bounds__(THREADS)
 k_gemm_tn(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K, int k_chunk,
-          float *__restrict__ partial, const int32_t *__restrict__ status) {
+          float *__restrict__ partial, const int32_t *__restrict__ status, const int32_t *__restrict__ k_dev) {
   if (*status != 0) return;
   constexpr int BK = Tile<T>::BK, LDK = Tile<T>::LDK;
+  if (k_dev) {
+    // the contraction length is only known on the device (at most K): the same split into gridDim.z
+    // ranges as the host would make; ranges beyond it are empty and leave a partial of zeros
+    K = min(max(*k_dev, 0), K);
+    k_chunk = (K + (int)gridDim.z - 1) / (int)gridDim.z;
+    k_chunk = max((k_chunk + BK - 1) / BK * BK, BK);
+  }
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   T *As = reinterpret_cast<T *>(smem);
   T *Bs = As + BM * LDK;
@@ -1039,13 +1046,13 @@ hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N,
 }
 
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
-                                 float *partial, const int32_t *status, hipStream_t s) {
+                                 float *partial, const int32_t *status, hipStream_t s, const int32_t *k_dev) {
   if (M <= 0 || N <= 0 || splits <= 0) return hipSuccess;
   const int bk = dtype == GEAR_BF16 ? Tile<bf16_t>::BK : Tile<float>::BK;
   int k_chunk = (K + splits - 1) / splits;
   k_chunk = ((k_chunk + bk - 1) / bk) * bk;
   if (k_chunk == 0) k_chunk = bk;
-  if (dtype == GEAR_BF16 && K % DK == 0 && M >= 8 && N >= 8) {
+  if (!k_dev && dtype == GEAR_BF16 && K % DK == 0 && M >= 8 && N >= 8) {
     const int kc = ((((K + splits - 1) / splits) + DK - 1) / DK) * DK;
     const dim3 grid_dma(((M + DM - 1) / DM) * ((N + DN - 1) / DN) * splits);
     hipLaunchKernelGGL(k_gemm_tn_dma, grid_dma, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, kc,
@@ -1055,10 +1062,10 @@ hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M,
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN), 1, splits);
   if (dtype == GEAR_BF16)
     hipLaunchKernelGGL(k_gemm_tn<bf16_t>, grid, dim3(THREADS), lds_bytes(2, Tile<bf16_t>::LDK), s, (const bf16_t *)A,
-                       (const bf16_t *)B, M, N, K, k_chunk, partial, status);
+                       (const bf16_t *)B, M, N, K, k_chunk, partial, status, k_dev);
   else
     hipLaunchKernelGGL(k_gemm_tn<float>, grid, dim3(THREADS), lds_bytes(4, Tile<float>::LDK), s, (const float *)A,
-                       (const float *)B, M, N, K, k_chunk, partial, status);
+                       (const float *)B, M, N, K, k_chunk, partial, status, k_dev);
   return hipGetLastError();
 }
 

@@ -455,7 +455,9 @@ __global__ void __launch_bounds__(kSortBlock) k_expired_scatter(const uint32_t *
 }
 
 __global__ void __launch_bounds__(256) k_stamp(int32_t *__restrict__ stamp, int64_t n_images,
-                                               const int32_t *__restrict__ ids, int64_t n, int32_t now, int32_t *status) {
+                                               const int32_t *__restrict__ ids, int64_t n, int32_t now, int32_t *status,
+                                               const int32_t *__restrict__ n_dev) {
+  if (n_dev) n = min((int64_t)max(*n_dev, 0), n);  // the row count is only known on the device
   for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += (int64_t)gridDim.x * blockDim.x) {
     const int64_t id = ids ? (int64_t)ids[r] : r;
     if (id < 0 || id >= n_images) {
@@ -489,11 +491,11 @@ hipError_t launch_expired(const int32_t *image_ids, int n, const int32_t *stamp,
 }
 
 hipError_t launch_stamp(int32_t *stamp, int64_t n_images, const int32_t *ids, int64_t n, int32_t now, int32_t *status,
-                        hipStream_t s) {
+                        hipStream_t s, const int32_t *n_dev) {
   if (n <= 0) return hipSuccess;
   int64_t want = (n + 255) / 256;
   const int blocks = (int)(want < 4096 ? want : 4096);
-  hipLaunchKernelGGL(k_stamp, dim3(blocks), dim3(256), 0, s, stamp, n_images, ids, n, now, status);
+  hipLaunchKernelGGL(k_stamp, dim3(blocks), dim3(256), 0, s, stamp, n_images, ids, n, now, status, n_dev);
   return hipGetLastError();
 }
 

@@ -296,6 +296,41 @@ def test_expired_ids_and_stamps_match_oracle():
     assert int((stamp != 77).sum().item()) == 0
 
 
+def test_refresh_and_stamp_with_the_count_on_the_device():
+    """gear_refresh_dfv_n / gear_stamp_dfv_n against the calls that take the count from the host: same
+    cache, same stamps, also when the list is empty and when the device word exceeds the capacity."""
+    wl = get_workload("hotkey").scaled(n_images=3000, batch=700)
+    src = PageViewSource(wl)
+    states = []
+    for on_device in (False, True):
+        cfg, st, _ = make_pair(wl)
+        stamp = torch.zeros(wl.n_images, dtype=torch.int32, device="cuda")
+        pool = torch.randn(wl.max_nnz, wl.dfv_dim, generator=torch.Generator().manual_seed(3)).cuda().to(st.dfv_cache.dtype)
+        for now, expiry in [(0, 1), (1, 1), (2, 3), (3, 50), (4, 2)]:
+            ids = torch.from_numpy(src.batch(now).img_id).cuda()
+            out, n_out = g.gear_expired_ids(st, ids, stamp, now, expiry)
+            if on_device:
+                g.gear_refresh_dfv_n(st, out, pool[: out.numel()], n_out)
+                g.gear_stamp_dfv_n(st, stamp, out, n_out, now)
+            else:
+                n = int(n_out.item())
+                if n:
+                    g.gear_refresh_dfv(st, out[:n], pool[:n])
+                    g.gear_stamp_dfv(st, stamp, out[:n], now)
+            torch.cuda.synchronize()
+            assert int(st.status.item()) == 0
+        states.append((st.dfv_cache.clone(), stamp.clone()))
+    assert torch.equal(states[0][0], states[1][0]) and torch.equal(states[0][1], states[1][1])
+    assert int((states[0][1] != 0).sum().item()) > 0
+    # a device word beyond the capacity is cut to the capacity
+    cfg, st, _ = make_pair(wl)
+    stamp = torch.zeros(wl.n_images, dtype=torch.int32, device="cuda")
+    ids = torch.tensor([7, 8, 9], dtype=torch.int32, device="cuda")
+    g.gear_stamp_dfv_n(st, stamp, ids, torch.tensor([1000], dtype=torch.int32, device="cuda"), 5)
+    torch.cuda.synchronize()
+    assert stamp.nonzero().flatten().tolist() == [7, 8, 9] and int(st.status.item()) == 0
+
+
 def test_expired_ids_over_several_tiles_of_images():
     """The same list against its definition (ascending distinct ids that are old enough) with an image
     count that spans several tiles of the filter's bitmap and ends inside a word."""
@@ -387,9 +422,10 @@ def test_adam_steps_free_running(name, batch, eps):
         params_close(f64(table[idx]), np.stack([store.row(int(k)) for k in ids]), f"adam {tag} rows", exempt=ex)
 
 
-@pytest.mark.parametrize("name", ["small", "bf16"])
-def test_dense_standin_closes_the_loop(name):
-    """Inference fills the cache, a step emits averaged gradients, the stand-in takes them (Eq. 1)."""
+@pytest.mark.parametrize("name,device_count", [("small", False), ("bf16", False), ("small", True), ("bf16", True)])
+def test_dense_standin_closes_the_loop(name, device_count):
+    """Inference fills the cache, a step emits averaged gradients, the stand-in takes them (Eq. 1).
+    device_count: the number of emissions stays on the device (gear_dense_backward_n)."""
     from oracle.dense_standin import DenseStandIn as OracleDense
     wl = get_workload(name).scaled(n_users=50_000, n_urls=1 << 15, n_images=3_000, M=4)
     batch, r = 900, 16
@@ -417,7 +453,10 @@ def test_dense_standin_closes_the_loop(name):
         fi.update(imgs)
         n = int(st.n_ready.item())
         emitted += n
-        dense.backward(st.ready_ids, st.ready_grads, n, 0.5)
+        if device_count:
+            dense.backward_n(st.ready_ids, st.ready_grads, st.n_ready, 0.5)
+        else:
+            dense.backward(st.ready_ids, st.ready_grads, n, 0.5)
         ref_dense.backward(ref.ready_ids, ref.ready_grads, 0.5)
         torch.cuda.synchronize()
         assert int(dense.status.item()) == 0
