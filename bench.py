@@ -79,12 +79,18 @@ class WorkModel:
         self.counts[img] += n_i
         with_img = int((np.diff(batch.img_off) > 0).sum())
         work = {}
+        wgrad_all = 0.0
         for l, (k, n) in enumerate(zip(self.lin, self.lout)):
             if l == len(self.lin) - 1:
                 break
             work[f"fwd_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)
             work[f"dgrad_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)
-            work[f"wgrad_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)
+            work[f"wgrad_gemm_l{l}"] = ("mfma", 2.0 * B * n * k)   # one launch per layer (not on this workload)
+            wgrad_all += 2.0 * B * n * k
+        # dLoss/dx comes from two products: the embedding slots, then the DFV slot
+        work["dgrad_gemm_emb"] = ("mfma", 2.0 * B * self.lout[0] * 2 * d)
+        work["dgrad_gemm_l0"] = ("mfma", 2.0 * B * self.lout[0] * D)
+        work["wgrad_gemm"] = ("mfma", wgrad_all)   # all hidden layers' weight gradients in one launch
         work["gather_pool"] = ("hbm", 12.0 * B + 4.0 * nnz + (uu + ul) * d * e_emb + len(img) * D * e_dfv
                                + B * F * e_act)
         work["embedding_update"] = ("hbm", 16.0 * B + 2.0 * B * d * 4 + 2.0 * (uu + ul) * d * e_emb)
@@ -103,9 +109,9 @@ TRAFFIC_KERNELS = {
     "fwd_gemm_l0": ("k_gemm_nt_dma<0>", 2, 0, ["gemm.hip"]),
     "fwd_gemm_l1": ("k_gemm_nt_dma<0>", 2, 1, ["gemm.hip"]),
     "dgrad_gemm_l1": ("k_gemm_nt_dma<4>", 1, 0, ["gemm.hip"]),   # masked by the sign bitmap
-    "dgrad_gemm_l0": ("k_gemm_nt_dma<3>", 1, 0, ["gemm.hip"]),
-    "wgrad_gemm_l1": ("k_gemm_tn_dma", 2, 0, ["gemm.hip"]),
-    "wgrad_gemm_l0": ("k_gemm_tn_dma", 2, 1, ["gemm.hip"]),
+    "dgrad_gemm_emb": ("k_gemm_nt_dma<3>", 2, 0, ["gemm.hip"]),
+    "dgrad_gemm_l0": ("k_gemm_nt_dma<3>", 2, 1, ["gemm.hip"]),
+    "wgrad_gemm": ("k_gemm_tn_dma_batch", 1, 0, ["gemm.hip"]),
 }
 
 

@@ -144,6 +144,17 @@ bool make_layout(const gear_config &c, Layout *lay) {
   lay->loss_partial = take(&cur, logit_partial_floats(lay->in_dim[L - 1]) * sizeof(float));
   lay->dx_emb = take(&cur, B * 2 * c.emb_dim * sizeof(float));
   lay->dx_dfv = take(&cur, B * c.dfv_dim * ab);
+  {
+    // all hidden layers' partials at once when their products go out as one launch
+    TnProblem wp[GEAR_MAX_LAYERS];
+    size_t all = 0;
+    for (int l = 0; l < L - 1; ++l) {
+      wp[l] = TnProblem{nullptr, nullptr, nullptr, lay->out_dim[l], lay->in_dim[l]};
+      all += (size_t)lay->in_dim[l] * lay->out_dim[l];
+    }
+    const size_t pb = (size_t)gemm_tn_batch_splits(c.mlp_dtype, wp, L - 1, c.max_batch) * all * sizeof(float);
+    if (pb > max_partial) max_partial = pb;
+  }
   lay->wgrad_partial = take(&cur, max_partial);
   lay->colsum_partial = take(&cur, (size_t)lay->colsum_chunks * max_h * sizeof(float));
   lay->emb_partial = take(&cur, embedding_partial_floats(c) * sizeof(float));
@@ -458,37 +469,72 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                                moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
     } else {
       // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type
-      GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_DX,
-                                         nullptr, dx_dfv, dx_emb, 2 * cfg->emb_dim, nullptr, nullptr, status, s));
+      // dLoss/dx in two products.  The embedding slots (fp32) come first, and as soon as they are
+      // there the SGD on the touched embedding rows starts on the helper stream, beside the larger
+      // product that makes the DFV slot (kept in the MLP's operand type).
+      const int E2 = 2 * cfg->emb_dim;
+      GEAR_RUN("dgrad_gemm_emb", launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, E2, lay.out_dim[0], EPI_DX,
+                                                nullptr, dx_dfv, dx_emb, E2, nullptr, nullptr, status, s));
+      if (side) {
+        GEAR_HIP(hipEventRecord(side->fork, s));
+        GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+      }
+      {
+        hipStream_t s = helper;
+        GEAR_RUN("embedding_update",
+                 launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
+                                         (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
+      }
+      GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0] + (size_t)E2 * lay.out_dim[0] * lay.act_bytes,
+                                         B, F - E2, lay.out_dim[0], EPI_DX, nullptr, dx_dfv, dx_emb, 0, nullptr, nullptr,
+                                         status, s));
     }
   }
 
-  // What only needs dLoss/dx goes to the helper stream: SGD on the touched embedding rows, then the
-  // per-image gradient bookkeeping.  Both are bound by memory traffic and run beside the
-  // weight-gradient products, which are not.  The bookkeeping comes second so that the products
-  // hold their CUs before its many small workgroups arrive: those fill what is left, whereas a
-  // product arriving later would wait for room among them.
+  // The per-image gradient bookkeeping only needs dLoss/dx and is bound by memory traffic: it runs on
+  // the helper stream beside the weight-gradient products, which are not.  The products are
+  // launched first and, where they can, as one launch of at most one round of workgroups, so that
+  // they hold their CUs before the bookkeeping's many small workgroups arrive and fill what is
+  // left; a product arriving later would wait until all of those have been placed.
   if (side) {
     GEAR_HIP(hipEventRecord(side->fork, s));
     GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
   }
   {
     hipStream_t s = helper;
-    GEAR_RUN("embedding_update",
-             launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
-                                     (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
     GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
                                              out->ready_grads, status, s));
   }
   if (side) GEAR_HIP(hipEventRecord(side->join, side->stream));
   // SGD on the hidden layers' weights: split-K wgrad (logit layer and all biases are done above)
-  for (int l = L - 2; l >= 0; --l) {
-    const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
-    GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
-                                              lay.in_dim[l], B, splits, wpart, status, s));
-    GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
-                                             t->mlp_params + lay.w_off[l], opt, moments_at(mom_mlp, lay.w_off[l]),
-                                             status, s));
+  TnProblem wp[GEAR_MAX_LAYERS];
+  int n_wp = 0;
+  for (int l = L - 2; l >= 0; --l)
+    wp[n_wp++] = TnProblem{ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], nullptr, lay.out_dim[l], lay.in_dim[l]};
+  const int batch_splits = gemm_tn_batch_splits(dt, wp, n_wp, B);
+  if (batch_splits > 0) {
+    float *next = wpart;
+    for (int i = 0; i < n_wp; ++i) {
+      wp[i].partial = next;
+      next += (size_t)batch_splits * wp[i].M * wp[i].N;
+    }
+    GEAR_RUN("wgrad_gemm", launch_gemm_tn_batch(wp, n_wp, B, batch_splits, status, s));
+    SplitkProblem sp[GEAR_MAX_LAYERS];
+    for (int i = 0; i < n_wp; ++i) {
+      const int l = L - 2 - i;
+      sp[i] = SplitkProblem{wp[i].partial, t->mlp_params + lay.w_off[l], moments_at(mom_mlp, lay.w_off[l]),
+                            (int64_t)wp[i].M * wp[i].N};
+    }
+    GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
+  } else {
+    for (int l = L - 2; l >= 0; --l) {
+      const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
+      GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
+                                                lay.in_dim[l], B, splits, wpart, status, s));
+      GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
+                                               t->mlp_params + lay.w_off[l], opt, moments_at(mom_mlp, lay.w_off[l]),
+                                               status, s));
+    }
   }
   if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
   if (out->dbg_img_unique && b->nnz > 0)

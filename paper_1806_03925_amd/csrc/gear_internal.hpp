@@ -233,6 +233,26 @@ hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, co
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
                                  float *partial, const int32_t *status, hipStream_t s, const int32_t *k_dev = nullptr);
 int gemm_splitk_for(int M, int N, int K);  // wgrad split count for a [M x N] result contracted over K
+// Several such contractions over the same K rows of bf16 operands in one launch, all with the same
+// number of k-ranges: partial_i[z][M_i x N_i].  gemm_tn_batch_splits gives that number (it looks at
+// M and N only), or 0 if the set has to go through one launch per problem.
+struct TnProblem {
+  const void *A, *B;
+  float *partial;
+  int M, N;
+};
+int gemm_tn_batch_splits(int dtype, const TnProblem *p, int count, int K);
+hipError_t launch_gemm_tn_batch(const TnProblem *p, int count, int K, int splits, const int32_t *status,
+                                hipStream_t s);
+// w_i <- update(w_i, sum_z partial_i[z]) for the results of such a launch, in one launch
+struct SplitkProblem {
+  const float *partial;
+  float *w;
+  Moments mom;
+  int64_t count;
+};
+hipError_t launch_splitk_sgd_batch(const SplitkProblem *p, int count, int splits, const Optim &opt,
+                                   const int32_t *status, hipStream_t s);
 hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, const Optim &opt,
                              const Moments &mom, const int32_t *status, hipStream_t s);
 

@@ -751,20 +751,14 @@ __device__ __forceinline__ void tn_main_loop(f32x16_v (&acc)[TM][TN], const bf16
   }
 }
 
-__global__ void __launch_bounds__(DTHREADS)
-k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K, int k_chunk,
-              float *__restrict__ partial, const int32_t *__restrict__ status) {
-  if (*status != 0) return;
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * TSTAGE];
-
+// One workgroup's share: tile `tile` of the [M x N] result over the k-range `split`, left in
+// partial[split][M x N].
+__device__ __forceinline__ void tn_dma_work(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N,
+                                            int K, int k_chunk, float *__restrict__ partial, int split, int tile,
+                                            unsigned char *lds) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
-  // one-dimensional grid of tiles x k-ranges; the workgroups of one XCD take neighbouring (range, tile)
-  // pairs, so the tiles that read the same rows of the batch share them in that XCD's L2
   const int n_tiles = (N + DN - 1) / DN;
-  const int tiles = ((M + DM - 1) / DM) * n_tiles;
-  const int work = xcd_remap(blockIdx.x, gridDim.x);
-  const int split = work / tiles, tile = work % tiles;
   const int m0 = (tile / n_tiles) * DM, n0 = (tile % n_tiles) * DN;
   const int k_begin = split * k_chunk;
   const int k_end = min(K, k_begin + k_chunk);
@@ -829,6 +823,40 @@ k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
         if (m < M && n < N) dst[(size_t)m * N + n] = acc[i][j][e];
       }
     }
+}
+
+__global__ void __launch_bounds__(DTHREADS)
+k_gemm_tn_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K, int k_chunk,
+              float *__restrict__ partial, const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * TSTAGE];
+  // one-dimensional grid of tiles x k-ranges; the workgroups of one XCD take neighbouring (range, tile)
+  // pairs, so the tiles that read the same rows of the batch share them in that XCD's L2
+  const int tiles = ((M + DM - 1) / DM) * ((N + DN - 1) / DN);
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  tn_dma_work(A, B, M, N, K, k_chunk, partial, work / tiles, work % tiles, lds);
+}
+
+// Several contractions over the same K rows in one launch: the grid is k-ranges x (all tiles of all
+// problems), so every workgroup does the same amount of work whichever result it belongs to.
+struct TnBatchArgs {
+  int count, tiles;
+  TnProblem p[GEAR_MAX_LAYERS];
+  int first_tile[GEAR_MAX_LAYERS];
+};
+
+__global__ void __launch_bounds__(DTHREADS)
+k_gemm_tn_dma_batch(TnBatchArgs args, int K, int k_chunk, const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * TSTAGE];
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int split = work / args.tiles, tile = work % args.tiles;
+  int which = 0;
+  for (int i = 1; i < args.count; ++i)
+    if (tile >= args.first_tile[i]) which = i;
+  const TnProblem &q = args.p[which];
+  tn_dma_work((const bf16_t *)q.A, (const bf16_t *)q.B, q.M, q.N, K, k_chunk, q.partial, split,
+              tile - args.first_tile[which], lds);
 }
 
 // ---- kernels ---------------------------------------------------------------------------------------
@@ -938,11 +966,8 @@ k_gemm_tn(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
 
 // W <- update(W, sum_z partial[z]), z ascending; a thread owns four consecutive elements (count is a
 // multiple of 4 because layer widths are multiples of 8) and keeps eight partials in flight
-__global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ partial, int splits, int64_t count,
-                                                    float *__restrict__ w, Optim opt, Moments mom,
-                                                    const int32_t *__restrict__ status) {
-  if (*status != 0) return;
-  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+__device__ __forceinline__ void splitk_sgd_at(const float *__restrict__ partial, int splits, int64_t count,
+                                              float *__restrict__ w, const Optim &opt, const Moments &mom, int64_t i) {
   if (i >= count) return;
   float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
   int z = 0;
@@ -970,6 +995,31 @@ __global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ pa
     *reinterpret_cast<float4 *>(mom.v + i) = v;
   }
   *reinterpret_cast<float4 *>(w + i) = cur;
+}
+
+__global__ void __launch_bounds__(256) k_splitk_sgd(const float *__restrict__ partial, int splits, int64_t count,
+                                                    float *__restrict__ w, Optim opt, Moments mom,
+                                                    const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  splitk_sgd_at(partial, splits, count, w, opt, mom, ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4);
+}
+
+// the same for the results of a batched launch: a workgroup belongs to one of them
+struct SplitkBatchArgs {
+  int count;
+  SplitkProblem p[GEAR_MAX_LAYERS];
+  int first_block[GEAR_MAX_LAYERS];
+};
+
+__global__ void __launch_bounds__(256) k_splitk_sgd_batch(SplitkBatchArgs args, int splits, Optim opt,
+                                                          const int32_t *__restrict__ status) {
+  if (*status != 0) return;
+  int which = 0;
+  for (int i = 1; i < args.count; ++i)
+    if ((int)blockIdx.x >= args.first_block[i]) which = i;
+  const SplitkProblem &q = args.p[which];
+  splitk_sgd_at(q.partial, splits, q.count, q.w, opt, q.mom,
+                ((int64_t)(blockIdx.x - args.first_block[which]) * blockDim.x + threadIdx.x) * 4);
 }
 
 template <typename T>
@@ -1045,6 +1095,43 @@ hipError_t launch_gemm_nt(int dtype, const void *A, const void *B, int M, int N,
              : run_nt<float>(A, B, M, N, K, epilogue_kind, bias, aux, out, split, colpart, relu_bits, status, s);
 }
 
+// Split count shared by the problems of a batched launch: one round of the 256 CUs, every range at
+// least 512 rows.  0 when the set does not go through the batched kernel.
+int gemm_tn_batch_splits(int dtype, const TnProblem *p, int count, int K) {
+  if (dtype != GEAR_BF16 || count < 2 || count > GEAR_MAX_LAYERS || K <= 0 || K % DK != 0) return 0;
+  int tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    if (p[i].M < 8 || p[i].N < 8) return 0;
+    tiles += ((p[i].M + DM - 1) / DM) * ((p[i].N + DN - 1) / DN);
+  }
+  if (tiles > 128) return 0;
+  int s = 256 / tiles;
+  const int cap = K / 512 < 1 ? 1 : K / 512;
+  if (s > cap) s = cap;
+  return s > 64 ? 64 : s;
+}
+
+hipError_t launch_gemm_tn_batch(const TnProblem *p, int count, int K, int splits, const int32_t *status,
+                                hipStream_t s) {
+  if (count < 1 || count > GEAR_MAX_LAYERS || splits < 1 || K % DK != 0) return hipErrorInvalidValue;
+  TnBatchArgs args;
+  args.count = count;
+  args.tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    if (p[i].M < 8 || p[i].N < 8 || !p[i].A || !p[i].B || !p[i].partial) return hipErrorInvalidValue;
+    args.p[i] = p[i];
+    args.first_tile[i] = args.tiles;
+    args.tiles += ((p[i].M + DM - 1) / DM) * ((p[i].N + DN - 1) / DN);
+  }
+  for (int i = count; i < GEAR_MAX_LAYERS; ++i) {
+    args.p[i] = TnProblem{nullptr, nullptr, nullptr, 0, 0};
+    args.first_tile[i] = args.tiles;
+  }
+  const int kc = ((((K + splits - 1) / splits) + DK - 1) / DK) * DK;
+  hipLaunchKernelGGL(k_gemm_tn_dma_batch, dim3(args.tiles * splits), dim3(DTHREADS), 0, s, args, K, kc, status);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
                                  float *partial, const int32_t *status, hipStream_t s, const int32_t *k_dev) {
   if (M <= 0 || N <= 0 || splits <= 0) return hipSuccess;
@@ -1074,6 +1161,22 @@ hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, fl
   if (count <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_splitk_sgd, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, s, partial, splits, count,
                      w, opt, mom, status);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_sgd_batch(const SplitkProblem *p, int count, int splits, const Optim &opt,
+                                   const int32_t *status, hipStream_t s) {
+  if (count < 1 || count > GEAR_MAX_LAYERS || splits < 1) return hipErrorInvalidValue;
+  SplitkBatchArgs args;
+  args.count = count;
+  int blocks = 0;
+  for (int i = 0; i < GEAR_MAX_LAYERS; ++i) {
+    args.p[i] = i < count ? p[i] : SplitkProblem{nullptr, nullptr, Moments{nullptr, nullptr}, 0};
+    args.first_block[i] = blocks;
+    if (i < count) blocks += (int)((p[i].count / 4 + 255) / 256);
+  }
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_splitk_sgd_batch, dim3(blocks), dim3(256), 0, s, args, splits, opt, status);
   return hipGetLastError();
 }
 

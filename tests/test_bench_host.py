@@ -31,7 +31,9 @@ def test_work_model_counts_what_a_step_has_to_move():
                       label=np.zeros(3, np.float32))
     w = model.step(b)
     B, nnz, d, D, F = 3, 4, 16, 64, 96
-    assert w["fwd_gemm_l0"] == ("mfma", 2.0 * B * 64 * F) == w["dgrad_gemm_l0"] == w["wgrad_gemm_l0"]
+    assert w["fwd_gemm_l0"] == ("mfma", 2.0 * B * 64 * F) == w["wgrad_gemm_l0"] == w["wgrad_gemm"]
+    # dLoss/dx is made by two products: the embedding slots (2 d columns), then the DFV slot (D columns)
+    assert w["dgrad_gemm_emb"] == ("mfma", 2.0 * B * 64 * 2 * d) and w["dgrad_gemm_l0"] == ("mfma", 2.0 * B * 64 * D)
     assert "fwd_gemm_l1" not in w                                # the logit layer is not a matrix product here
     # gather: ids and offsets, each distinct row once (2 users, 2 urls, 2 images), x written once
     assert w["gather_pool"] == ("hbm", 12.0 * B + 4.0 * nnz + 4 * d * 4 + 2 * D * 4 + B * F * 4)
@@ -63,7 +65,7 @@ def test_counter_files_become_bytes_per_launch(tmp_path, monkeypatch):
     ns = "void gear::(anonymous namespace)::"
     step = [("k_gather_pool<float, unsigned short, unsigned short>(int)", 10.0), ("k_gemm_nt_dma<0>(x)", 20.0),
             ("k_gemm_nt_dma<0>(x)", 30.0), ("k_gemm_nt_dma<4>(x)", 40.0), ("k_gemm_nt_dma<3>(x)", 50.0),
-            ("k_gemm_tn_dma(x)", 60.0), ("k_gemm_tn_dma(x)", 70.0), ("k_accumulate<unsigned short>(x)", 80.0)]
+            ("k_gemm_nt_dma<3>(x)", 60.0), ("k_gemm_tn_dma_batch(x)", 70.0), ("k_accumulate<unsigned short>(x)", 80.0)]
     rows = [(ns + n, v) for n, v in step] + [(ns + n, v + 2.0) for n, v in step] + [(ns + "k_refresh(x)", 1000.0)]
     _counter_csv(tmp_path / "f.csv", "FETCH_SIZE", rows)
     _counter_csv(tmp_path / "w.csv", "WRITE_SIZE", [(n, 2 * v) for n, v in rows])
@@ -71,9 +73,11 @@ def test_counter_files_become_bytes_per_launch(tmp_path, monkeypatch):
     rec = json.load(open(tmp_path / "traffic.json"))
     assert rec["calibration"] == {"fetch_bytes_per_count": 4.0, "write_bytes_per_count": 2.0}
     k = rec["kernels"]
-    # launches of one kernel inside a step are told apart by their order: fwd l0 is the first NT<0>, wgrad l1 the first TN
+    # launches of one kernel inside a step are told apart by their order: fwd l0 is the first NT<0>, the
+    # embedding slots of dLoss/dx the first NT<3>
     assert k["fwd_gemm_l0"]["fetch_bytes"] == 4.0 * 21.0 and k["fwd_gemm_l1"]["fetch_bytes"] == 4.0 * 31.0
-    assert k["wgrad_gemm_l1"]["fetch_bytes"] == 4.0 * 61.0 and k["wgrad_gemm_l0"]["write_bytes"] == 2.0 * 142.0
+    assert k["dgrad_gemm_emb"]["fetch_bytes"] == 4.0 * 51.0 and k["dgrad_gemm_l0"]["fetch_bytes"] == 4.0 * 61.0
+    assert k["wgrad_gemm"]["write_bytes"] == 2.0 * 142.0
     assert k["accumulate"]["bytes"] == 4.0 * 81.0 + 2.0 * 162.0 and k["accumulate"]["launches"] == 2
     assert "accumulate" in open(tmp_path / "traffic.txt").read()
     # a record is only reported while the kernel's source is the one it was taken on

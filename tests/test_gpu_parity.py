@@ -240,6 +240,24 @@ def test_wide_and_narrow_last_hidden_layer(dtype, hidden):
     check_state(wl, st, orc, f"{dtype} hidden {hidden}")
 
 
+@pytest.mark.parametrize("batch", [1056, 389])
+def test_three_hidden_layers(batch):
+    """Weight gradients of all hidden layers: in one launch over two ragged ranges of the batch (1056 = 33 * 32
+    rows, result tiles of 320 and 72 rows and columns) or, for a batch that is no multiple of the
+    k-tile, one launch per layer."""
+    wl = get_workload("tiny").scaled(layers=(320, 72, 64, 1), mlp_dtype="bf16", emb_dtype="bf16", dfv_dtype="bf16",
+                                     batch=1056)
+    cfg, st, orc = make_pair(wl)
+    src = PageViewSource(wl)
+    fu, fl, fi = set(), set(), set()
+    for step in range(2):
+        b = src.batch(step, batch=batch)
+        ref, fv, imgs = check_step(wl, st, orc, b, 0.5, f"three hidden layers B={batch} step {step}",
+                                   earlier_flipped_imgs=fi)
+        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
+    check_state(wl, st, orc, f"three hidden layers B={batch}", fu, fl, fi)
+
+
 def test_epoch_pattern_free_running():
     """One image per view, every image once per epoch: cold rows each step, groups close after M epochs."""
     wl = get_workload("epoch").scaled(batch=600, n_images=1800, M=2)
