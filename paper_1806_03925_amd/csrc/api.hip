@@ -202,6 +202,10 @@ struct SideLane {
 SideLane g_side[64];
 std::mutex g_side_mutex;
 
+// multiply-adds of the DFV-slot part of the dLoss/dx product from which it is worth an extra launch
+// and event to let the embedding update run beside it (about 10 us of work on the device)
+constexpr double kSplitDxMacs = 5e9;
+
 // the helper lane of the current device; nullptr when one of its objects cannot be created (nothing
 // half-made is kept: the next call starts over)
 SideLane *side_lane() {
@@ -452,6 +456,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   float *dx_emb = (float *)(ws + lay.dx_emb);
   void *dx_dfv = ws + lay.dx_dfv;
   float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
+  bool embedding_updated = false;
   for (int l = L - 2; l >= 0; --l) {
     if (l > 0) {
       const int parts = gemm_nt_colsum_parts(dt, B, lay.in_dim[l], lay.out_dim[l]);
@@ -468,26 +473,33 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                                t->mlp_params + lay.b_off[l - 1], opt,
                                                moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
     } else {
-      // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type
-      // dLoss/dx in two products.  The embedding slots (fp32) come first, and as soon as they are
-      // there the SGD on the touched embedding rows starts on the helper stream, beside the larger
-      // product that makes the DFV slot (kept in the MLP's operand type).
+      // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type.
+      // When the product is long enough to hide it, it is made in two parts: the embedding slots
+      // first, and as soon as they are there the SGD on the touched embedding rows starts on the
+      // helper stream, beside the larger product that makes the DFV slot.  Every element is computed
+      // the same way in both forms.
       const int E2 = 2 * cfg->emb_dim;
-      GEAR_RUN("dgrad_gemm_emb", launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, E2, lay.out_dim[0], EPI_DX,
-                                                nullptr, dx_dfv, dx_emb, E2, nullptr, nullptr, status, s));
-      if (side) {
-        GEAR_HIP(hipEventRecord(side->fork, s));
-        GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+      if ((double)B * (F - E2) * lay.out_dim[0] >= kSplitDxMacs) {
+        GEAR_RUN("dgrad_gemm_emb", launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, E2, lay.out_dim[0], EPI_DX,
+                                                  nullptr, dx_dfv, dx_emb, E2, nullptr, nullptr, status, s));
+        if (side) {
+          GEAR_HIP(hipEventRecord(side->fork, s));
+          GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+        }
+        {
+          hipStream_t s = helper;
+          GEAR_RUN("embedding_update",
+                   launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
+                                           (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
+        }
+        embedding_updated = true;
+        GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0],
+                                           ws + lay.wct[0] + (size_t)E2 * lay.out_dim[0] * lay.act_bytes, B, F - E2,
+                                           lay.out_dim[0], EPI_DX, nullptr, dx_dfv, dx_emb, 0, nullptr, nullptr, status, s));
+      } else {
+        GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, F, lay.out_dim[0], EPI_DX,
+                                           nullptr, dx_dfv, dx_emb, E2, nullptr, nullptr, status, s));
       }
-      {
-        hipStream_t s = helper;
-        GEAR_RUN("embedding_update",
-                 launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
-                                         (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
-      }
-      GEAR_RUN(kDgrad[0], launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0] + (size_t)E2 * lay.out_dim[0] * lay.act_bytes,
-                                         B, F - E2, lay.out_dim[0], EPI_DX, nullptr, dx_dfv, dx_emb, 0, nullptr, nullptr,
-                                         status, s));
     }
   }
 
@@ -502,6 +514,10 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   }
   {
     hipStream_t s = helper;
+    if (!embedding_updated)
+      GEAR_RUN("embedding_update",
+               launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
+                                       (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
     GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
                                              out->ready_grads, status, s));
   }

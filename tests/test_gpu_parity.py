@@ -240,6 +240,20 @@ def test_wide_and_narrow_last_hidden_layer(dtype, hidden):
     check_state(wl, st, orc, f"{dtype} hidden {hidden}")
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_a_product_made_in_two_column_parts_has_the_same_bits(dtype):
+    """A step makes dLoss/dx either as one product or as two (embedding slots, DFV slot), depending on
+    its size: an element must not depend on which tile of which launch it falls into."""
+    gen = torch.Generator().manual_seed(7)
+    A = torch.randn(777, 1024, generator=gen).to(dtype).cuda()
+    W = (torch.randn(1152, 1024, generator=gen) / 32).to(dtype).cuda()     # rows = columns of the result
+    whole = g.gear_gemm(A, W, 0)
+    left = g.gear_gemm(A, W[:128].contiguous(), 0)
+    right = g.gear_gemm(A, W[128:].contiguous(), 0)
+    torch.cuda.synchronize()
+    assert torch.equal(whole[:, :128], left) and torch.equal(whole[:, 128:], right)
+
+
 @pytest.mark.parametrize("batch", [1056, 389])
 def test_three_hidden_layers(batch):
     """Weight gradients of all hidden layers: in one launch over two ragged ranges of the batch (1056 = 33 * 32
