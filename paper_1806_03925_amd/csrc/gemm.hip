@@ -550,7 +550,10 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
               colacc[2 * w + 1] += __uint_as_float(v.w[w] & 0xffff0000u);
             }
           }
-          *reinterpret_cast<uint4 *>(out_bf + (size_t)m * ld_bf + (n_vec - col_shift)) = v.u;
+          // streamed out: nobody on this XCD reads these lines again before they would be evicted,
+          // and operand lines that other tiles are about to share stay in its L2 instead
+          __builtin_nontemporal_store(u32x4_v{v.u.x, v.u.y, v.u.z, v.u.w},
+                                      reinterpret_cast<u32x4_v *>(out_bf + (size_t)m * ld_bf + (n_vec - col_shift)));
         }
       }
       __builtin_amdgcn_wave_barrier();
