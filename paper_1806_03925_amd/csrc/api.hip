@@ -156,7 +156,8 @@ bool make_layout(const gear_config &c, Layout *lay) {
     if (pb > max_partial) max_partial = pb;
   }
   lay->wgrad_partial = take(&cur, max_partial);
-  lay->colsum_partial = take(&cur, (size_t)lay->colsum_chunks * max_h * sizeof(float));
+  lay->colsum_stride = (size_t)lay->colsum_chunks * max_h;   // one buffer per hidden layer: they are reduced at the end of a step
+  lay->colsum_partial = take(&cur, lay->colsum_stride * (size_t)(L > 1 ? L - 1 : 1) * sizeof(float));
   lay->emb_partial = take(&cur, embedding_partial_floats(c) * sizeof(float));
   lay->occ_view = take(&cur, NNZ * sizeof(int32_t));
   for (int s = 0; s < kMaxProblems; ++s) {
@@ -191,12 +192,12 @@ bool make_layout(const gear_config &c, Layout *lay) {
 
 using namespace gear;
 
-// One helper stream and three events per device, created on first use and kept for the life of the
+// One helper stream and two events per device, created on first use and kept for the life of the
 // process: the integer grouping of a step runs beside its gather and forward pass.
 namespace {
 struct SideLane {
   hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr, cast = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
   bool ready = false;
 };
 SideLane g_side[64];
@@ -218,9 +219,7 @@ SideLane *side_lane() {
     bool ok = hipStreamCreateWithFlags(&made.stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&made.fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&made.join, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&made.cast, hipEventDisableTiming) == hipSuccess;
     if (!ok) {
-      if (made.cast) (void)hipEventDestroy(made.cast);
       if (made.join) (void)hipEventDestroy(made.join);
       if (made.fork) (void)hipEventDestroy(made.fork);
       if (made.stream) (void)hipStreamDestroy(made.stream);
@@ -395,9 +394,8 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   plan.row_view = (int32_t *)(ws + lay.row_view);
   plan.row_scale = (float *)(ws + lay.row_scale);
   plan.n_units = (int32_t *)(ws + lay.n_units);
-  // What depends only on ids, counters and pre-step parameters runs on the helper stream while the main
-  // stream gathers and runs the forward pass: the check of the ids, operand copies of the weights
-  // (needed by the first product), the grouping, the accumulation plan and the counter update.  The
+  // What depends only on ids and counters runs on the helper stream while the main stream gathers and
+  // runs the forward pass: the check of the ids, the grouping, the accumulation plan and the counter update.  The
   // main stream waits for it before the first kernel that changes caller state, so the status word
   // is final by then; until then its kernels write the workspace only, and the gather clamps what it
   // uses as an index.
@@ -410,15 +408,21 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
   }
   {
+    // operand copies of the weights (all layers in one launch), ahead of the gather on the caller's
+    // stream: the first product then needs no event, and behind the gather's many workgroups the
+    // copies would not get onto the device before it ends anyway
+    const float *cw[GEAR_MAX_LAYERS];
+    void *cwc[GEAR_MAX_LAYERS], *cwct[GEAR_MAX_LAYERS];
+    for (int l = 0; l < L; ++l) {
+      cw[l] = t->mlp_params + lay.w_off[l];
+      cwc[l] = ws + lay.wc[l];
+      cwct[l] = ws + lay.wct[l];
+    }
+    GEAR_RUN("cast_weights", launch_cast_weights(L, cw, lay.out_dim, lay.in_dim, dt, cwc, cwct, status, s));
+  }
+  {
     hipStream_t s = helper;  // the launches of this block go to the helper stream
     GEAR_RUN("validate", launch_validate(*cfg, *b, occ_view, status, s));
-    {
-      Span span_(prof, "cast_weights", s);
-      for (int l = 0; l < L; ++l)
-        GEAR_HIP(launch_cast_weights(t->mlp_params + lay.w_off[l], lay.out_dim[l], lay.in_dim[l], dt,
-                                     ws + lay.wc[l], ws + lay.wct[l], status, s));
-    }
-    if (side) GEAR_HIP(hipEventRecord(side->cast, s));
     GEAR_RUN("group_ids", launch_group(gb, status, s));
     GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap,
                                              out->n_ready, status, s));
@@ -428,8 +432,13 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
 
   // forward
   void *x = ws + lay.x;
+  // the weight-gradient products of the hidden layers, and whether they go out as one launch
+  TnProblem wp[GEAR_MAX_LAYERS];
+  int n_wp = 0;
+  for (int l = L - 2; l >= 0; --l)
+    wp[n_wp++] = TnProblem{ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], nullptr, lay.out_dim[l], lay.in_dim[l]};
+  const int batch_splits = gemm_tn_batch_splits(dt, wp, n_wp, B);
   GEAR_RUN("gather_pool", launch_gather_pool(*cfg, *b, *t, dfv_cache, x, s));
-  if (side) GEAR_HIP(hipStreamWaitEvent(s, side->cast, 0));
   // A hidden layer below the last one also leaves the sign bitmap of its activations when both its
   // own product and the dgrad product that masks with it run in the kernel that knows bitmaps: the
   // backward pass then reads one bit per unit instead of the activation.
@@ -442,20 +451,44 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
                                      ws + lay.h[l], 0, nullptr, relu_bits[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
-  if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // status is final from here on
-  GEAR_RUN("logit_loss_sgd",
-           launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.w_off[L - 1],
-                             t->mlp_params + lay.b_off[L - 1], t->mlp_params + lay.b_off[L - 2], b->label, B,
-                             lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2], (float *)(ws + lay.loss_partial),
-                             out->loss, opt, moments_at(mom_mlp, lay.w_off[L - 1]), moments_at(mom_mlp, lay.b_off[L - 1]),
-                             moments_at(mom_mlp, lay.b_off[L - 2]), status, s));
+  // Until its first kernel that changes caller state, the caller's stream writes the workspace only
+  // and need not know whether the ids were in range or the ready list fits.  With one launch for
+  // all weight gradients that kernel is the last one of the step, behind the final join; otherwise
+  // the stream waits here for the helper's first part, so that the status word is final.
+  if (side && batch_splits == 0) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));
+  GEAR_RUN("logit_loss", launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1],
+                                           b->label, B, lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2],
+                                           (float *)(ws + lay.loss_partial), status, s));
 
   // backward through the hidden layers down to dLoss/dx (all from the pre-step operand copies)
   // Each product that makes the delta of a hidden layer also leaves that layer's bias gradient (column
-  // sums of the delta) as per-row-tile partials, which are added in tile order and applied at once.
+  // sums of the delta) as per-row-tile partials; they are added in tile order at the end of the step.
   float *dx_emb = (float *)(ws + lay.dx_emb);
   void *dx_dfv = ws + lay.dx_dfv;
   float *cpart = (float *)(ws + lay.colsum_partial), *wpart = (float *)(ws + lay.wgrad_partial);
+  // Small reductions whose results nothing in the step reads (the loss, SGD on the logit layer and on
+  // the biases): they go to the helper stream, ahead of the embedding update.
+  auto small_reductions = [&](hipStream_t s) -> gear_status {
+    GEAR_RUN("logit_sgd", launch_logit_finish((float *)(ws + lay.loss_partial), B, lay.in_dim[L - 1],
+                                              t->mlp_params + lay.w_off[L - 1], t->mlp_params + lay.b_off[L - 1],
+                                              t->mlp_params + lay.b_off[L - 2], out->loss, opt,
+                                              moments_at(mom_mlp, lay.w_off[L - 1]), moments_at(mom_mlp, lay.b_off[L - 1]),
+                                              moments_at(mom_mlp, lay.b_off[L - 2]), status, s));
+    for (int l = L - 2; l > 0; --l) {
+      // bias gradient of layer l - 1: column sums of its delta, left as per-row-tile partials by the
+      // product that made it where that kernel does so, otherwise summed here
+      const int parts = gemm_nt_colsum_parts(dt, B, lay.in_dim[l], lay.out_dim[l]);
+      if (parts)
+        GEAR_RUN("bias_sgd", launch_partial_sgd(cpart + (size_t)l * lay.colsum_stride, parts, lay.out_dim[l - 1],
+                                                t->mlp_params + lay.b_off[l - 1], opt,
+                                                moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
+      else
+        GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l - 1], B, lay.out_dim[l - 1], cpart,
+                                               t->mlp_params + lay.b_off[l - 1], opt,
+                                               moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
+    }
+    return GEAR_OK;
+  };
   bool embedding_updated = false;
   for (int l = L - 2; l >= 0; --l) {
     if (l > 0) {
@@ -464,14 +497,8 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
       GEAR_RUN(kDgrad[l], launch_gemm_nt(dt, ws + lay.delta[l], ws + lay.wct[l], B, lay.in_dim[l], lay.out_dim[l],
                                          by_bits ? EPI_MASK_BITS : EPI_MASK, nullptr,
                                          by_bits ? (const void *)relu_bits[l - 1] : (const void *)(ws + lay.h[l - 1]),
-                                         ws + lay.delta[l - 1], 0, parts ? cpart : nullptr, nullptr, status, s));
-      if (parts)
-        GEAR_RUN("bias_sgd", launch_partial_sgd(cpart, parts, lay.out_dim[l - 1], t->mlp_params + lay.b_off[l - 1], opt,
-                                                moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
-      else
-        GEAR_RUN("bias_sgd", launch_colsum_sgd(dt, ws + lay.delta[l - 1], B, lay.out_dim[l - 1], cpart,
-                                               t->mlp_params + lay.b_off[l - 1], opt,
-                                               moments_at(mom_mlp, lay.b_off[l - 1]), status, s));
+                                         ws + lay.delta[l - 1], 0, parts ? cpart + (size_t)l * lay.colsum_stride : nullptr, nullptr,
+                                         status, s));
     } else {
       // dLoss/dx: the embedding slots stay fp32, the DFV slot is kept in the MLP's operand type.
       // When the product is long enough to hide it, it is made in two parts: the embedding slots
@@ -488,6 +515,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
         }
         {
           hipStream_t s = helper;
+          if (gear_status st = small_reductions(s)) return st;
           GEAR_RUN("embedding_update",
                    launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
                                            (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
@@ -514,20 +542,18 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   }
   {
     hipStream_t s = helper;
-    if (!embedding_updated)
+    if (!embedding_updated) {
+      if (gear_status st = small_reductions(s)) return st;
       GEAR_RUN("embedding_update",
                launch_embedding_update(*cfg, gb.p[0], gb.p[1], dx_emb, t->user_emb, t->url_emb,
                                        (float *)(ws + lay.emb_partial), opt, mom_user, mom_url, status, s));
+    }
     GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
                                              out->ready_grads, status, s));
   }
   if (side) GEAR_HIP(hipEventRecord(side->join, side->stream));
-  // SGD on the hidden layers' weights: split-K wgrad (logit layer and all biases are done above)
-  TnProblem wp[GEAR_MAX_LAYERS];
-  int n_wp = 0;
-  for (int l = L - 2; l >= 0; --l)
-    wp[n_wp++] = TnProblem{ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], nullptr, lay.out_dim[l], lay.in_dim[l]};
-  const int batch_splits = gemm_tn_batch_splits(dt, wp, n_wp, B);
+  // SGD on the hidden layers' weights: split-K wgrad (the logit layer and all biases are done on the helper stream)
+  bool joined = false;
   if (batch_splits > 0) {
     float *next = wpart;
     for (int i = 0; i < n_wp; ++i) {
@@ -541,6 +567,10 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
       sp[i] = SplitkProblem{wp[i].partial, t->mlp_params + lay.w_off[l], moments_at(mom_mlp, lay.w_off[l]),
                             (int64_t)wp[i].M * wp[i].N};
     }
+    // the step's work on the helper stream ends here; the sums of the partials and the SGD follow it
+    // (they would not get onto the device before the bookkeeping's workgroups are all placed anyway)
+    if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));
+    joined = true;
     GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
   } else {
     for (int l = L - 2; l >= 0; --l) {
@@ -552,7 +582,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                                status, s));
     }
   }
-  if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
+  if (side && !joined) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
   if (out->dbg_img_unique && b->nnz > 0)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_unique, gb.p[2].unique, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_img_segoff)

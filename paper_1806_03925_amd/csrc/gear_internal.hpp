@@ -162,6 +162,7 @@ struct Layout {
   size_t x, h[GEAR_MAX_LAYERS], delta[GEAR_MAX_LAYERS], logits, dz, loss_partial, dx_emb, dx_dfv;
   size_t relu_bits[GEAR_MAX_LAYERS];  // [B x out/8] sign bitmaps of the hidden activations
   size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial, emb_partial;
+  size_t colsum_stride;              // floats between the column-sum partials of consecutive layers
   size_t occ_view;
   struct G {
     size_t keys[2], vals[2], block_hist, tile_heads, unique, segoff, pos_seg, n_unique;
@@ -206,8 +207,8 @@ hipError_t launch_accum_plan(const GroupProblem &img, const AccumPlan &plan, con
 hipError_t launch_gather_pool(const gear_config &cfg, const gear_batch &b, const gear_tables &t,
                               const void *dfv_cache, void *x, hipStream_t s);
 
-hipError_t launch_cast_weights(const float *w, int rows, int cols, int dtype, void *wc, void *wct,
-                               const int32_t *status, hipStream_t s);
+hipError_t launch_cast_weights(int count, const float *const *w, const int *rows, const int *cols, int dtype,
+                               void *const *wc, void *const *wct, const int32_t *status, hipStream_t s);
 
 enum GemmEpilogue {
   EPI_BIAS_RELU = 0,  // out(T)   = max(acc + bias[n], 0)
@@ -256,11 +257,12 @@ hipError_t launch_splitk_sgd_batch(const SplitkProblem *p, int count, int splits
 hipError_t launch_splitk_sgd(const float *partial, int splits, int64_t count, float *w, const Optim &opt,
                              const Moments &mom, const int32_t *status, hipStream_t s);
 
-hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
-                             float *bias_hidden, const float *label, int B, int H, float *logits, float *dz,
-                             void *delta, float *partials, float *loss, const Optim &opt, const Moments &mom_w_last,
-                             const Moments &mom_bias_last, const Moments &mom_bias_hidden, const int32_t *status,
-                             hipStream_t s);
+hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, const float *bias_last, const float *label,
+                             int B, int H, float *logits, float *dz, void *delta, float *partials,
+                             const int32_t *status, hipStream_t s);
+hipError_t launch_logit_finish(float *partials, int B, int H, float *w_last, float *bias_last, float *bias_hidden,
+                               float *loss, const Optim &opt, const Moments &mom_w_last, const Moments &mom_bias_last,
+                               const Moments &mom_bias_hidden, const int32_t *status, hipStream_t s);
 size_t logit_partial_floats(int H);
 
 hipError_t launch_colsum_sgd(int dtype, const void *src, int B, int H, float *partial, float *dst, const Optim &opt,

@@ -8,13 +8,27 @@ namespace gear {
 namespace {
 
 // wc = W as MLP operands [rows x cols], wct = its transpose [cols x rows]; both from the fp32 master.
+// One launch serves all layers: a workgroup owns a 32 x 32 tile of one of them.
+struct CastArgs {
+  int count;
+  const float *w[GEAR_MAX_LAYERS];
+  void *wc[GEAR_MAX_LAYERS], *wct[GEAR_MAX_LAYERS];
+  int rows[GEAR_MAX_LAYERS], cols[GEAR_MAX_LAYERS], first_block[GEAR_MAX_LAYERS];
+};
+
 template <typename T>
-__global__ void __launch_bounds__(256) k_cast_weights(const float *__restrict__ w, int rows, int cols,
-                                                      T *__restrict__ wc, T *__restrict__ wct,
-                                                      const int32_t *__restrict__ status) {
+__global__ void __launch_bounds__(256) k_cast_weights(CastArgs args, const int32_t *__restrict__ status) {
   if (*status != 0) return;
   __shared__ float tile[32][33];
-  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  int which = 0;
+  for (int i = 1; i < args.count; ++i)
+    if ((int)blockIdx.x >= args.first_block[i]) which = i;
+  const int rows = args.rows[which], cols = args.cols[which];
+  const float *__restrict__ w = args.w[which];
+  T *__restrict__ wc = static_cast<T *>(args.wc[which]);
+  T *__restrict__ wct = static_cast<T *>(args.wct[which]);
+  const int local = blockIdx.x - args.first_block[which], col_tiles = (cols + 31) / 32;
+  const int c0 = (local % col_tiles) * 32, r0 = (local / col_tiles) * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
   for (int rr = ty; rr < 32; rr += 8) {
     const int r = r0 + rr, c = c0 + tx;
@@ -321,13 +335,27 @@ k_logit_finish(const float *__restrict__ part_w, const float *__restrict__ part_
 
 }  // namespace
 
-hipError_t launch_cast_weights(const float *w, int rows, int cols, int dtype, void *wc, void *wct,
-                               const int32_t *status, hipStream_t s) {
-  const dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+hipError_t launch_cast_weights(int count, const float *const *w, const int *rows, const int *cols, int dtype,
+                               void *const *wc, void *const *wct, const int32_t *status, hipStream_t s) {
+  if (count < 1 || count > GEAR_MAX_LAYERS) return hipErrorInvalidValue;
+  CastArgs args;
+  args.count = count;
+  int blocks = 0;
+  for (int i = 0; i < GEAR_MAX_LAYERS; ++i) {
+    const bool in = i < count;
+    args.w[i] = in ? w[i] : nullptr;
+    args.wc[i] = in ? wc[i] : nullptr;
+    args.wct[i] = in ? wct[i] : nullptr;
+    args.rows[i] = in ? rows[i] : 0;
+    args.cols[i] = in ? cols[i] : 0;
+    args.first_block[i] = blocks;
+    if (in) blocks += ((cols[i] + 31) / 32) * ((rows[i] + 31) / 32);
+  }
+  if (blocks == 0) return hipSuccess;
   if (dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_cast_weights<bf16_t>, grid, dim3(256), 0, s, w, rows, cols, (bf16_t *)wc, (bf16_t *)wct, status);
+    hipLaunchKernelGGL(k_cast_weights<bf16_t>, dim3(blocks), dim3(256), 0, s, args, status);
   else
-    hipLaunchKernelGGL(k_cast_weights<float>, grid, dim3(256), 0, s, w, rows, cols, (float *)wc, (float *)wct, status);
+    hipLaunchKernelGGL(k_cast_weights<float>, dim3(blocks), dim3(256), 0, s, args, status);
   return hipGetLastError();
 }
 
@@ -337,11 +365,9 @@ int logit_blocks(int B) {
 }
 
 // Forward logit + loss + delta of the last hidden layer, then SGD on the logit layer's weight and bias.
-hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, float *w_last, float *bias_last,
-                             float *bias_hidden, const float *label, int B, int H, float *logits, float *dz,
-                             void *delta, float *partials, float *loss, const Optim &opt, const Moments &mom_w_last,
-                             const Moments &mom_bias_last, const Moments &mom_bias_hidden, const int32_t *status,
-                             hipStream_t s) {
+hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, const float *bias_last, const float *label,
+                             int B, int H, float *logits, float *dz, void *delta, float *partials,
+                             const int32_t *status, hipStream_t s) {
   if (B <= 0) return hipSuccess;
   const int blocks = logit_blocks(B);
   const int rows_per_block = (B + blocks - 1) / blocks;
@@ -369,6 +395,18 @@ hipError_t launch_logit_loss(int dtype, const void *h, const void *wc_last, floa
   }
 #undef GEAR_LOGIT_T
 #undef GEAR_LOGIT
+  return hipGetLastError();
+}
+
+// The sums the launch above left in `partials`: the loss, and SGD on the logit layer's weights, its
+// bias and the bias of the last hidden layer.  Nothing later in a step reads what this writes.
+hipError_t launch_logit_finish(float *partials, int B, int H, float *w_last, float *bias_last, float *bias_hidden,
+                               float *loss, const Optim &opt, const Moments &mom_w_last, const Moments &mom_bias_last,
+                               const Moments &mom_bias_hidden, const int32_t *status, hipStream_t s) {
+  if (B <= 0) return hipSuccess;
+  const int blocks = logit_blocks(B);
+  float *part_w = partials, *part_d = part_w + (size_t)kLossBlocks * H, *part_b = part_d + (size_t)kLossBlocks * H,
+        *part_loss = part_b + kLossBlocks;
   hipLaunchKernelGGL(k_logit_finish, dim3((H + 7) / 8, 4), dim3(256), 0, s, part_w, part_d, part_b, part_loss, blocks,
                      H, B, w_last, bias_hidden, bias_last, loss, opt, mom_w_last, mom_bias_hidden, mom_bias_last, status);
   return hipGetLastError();
