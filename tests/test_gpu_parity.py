@@ -652,8 +652,17 @@ def test_maximum_batch_and_nnz():
     check_state(wl, st, orc, "max sizes")
 
 
-def test_bad_ids_are_reported_and_change_nothing():
+def _error_path_workload(one_launch):
+    """tiny as it is (fp32, one hidden layer: weight gradients layer by layer, the caller's stream waits
+    for the check of the ids before the loss), or with two bf16 hidden layers (all weight gradients in
+    one launch, the caller's stream joins the helper only before their SGD)."""
     wl = get_workload("tiny")
+    return wl.scaled(layers=(64, 32, 1), mlp_dtype="bf16") if one_launch else wl
+
+
+@pytest.mark.parametrize("one_launch", [False, True])
+def test_bad_ids_are_reported_and_change_nothing(one_launch):
+    wl = _error_path_workload(one_launch)
     cfg, st, _ = make_pair(wl)
     src = PageViewSource(wl)
     g.gear_step(st, g.DeviceBatch.from_host(src.batch(0)), wl.M, wl.lr)
@@ -677,8 +686,9 @@ def test_bad_ids_are_reported_and_change_nothing():
     assert int(st.status.item()) == 0 and not torch.equal(before[4], st.counts)
 
 
-def test_ready_list_over_capacity_is_reported_and_changes_nothing():
-    wl = get_workload("tiny").scaled(M=1)
+@pytest.mark.parametrize("one_launch", [False, True])
+def test_ready_list_over_capacity_is_reported_and_changes_nothing(one_launch):
+    wl = _error_path_workload(one_launch).scaled(M=1)
     cfg, st, _ = make_pair(wl, ready_cap=100)
     before = [t.clone() for t in (st.user_emb, st.mlp_params, st.grad_accum, st.counts)]
     g.gear_step(st, g.DeviceBatch.from_host(PageViewSource(wl).batch(0)), wl.M, wl.lr)   # nnz > 100 emissions
