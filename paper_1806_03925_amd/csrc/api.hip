@@ -152,10 +152,14 @@ bool make_layout(const gear_config &c, Layout *lay) {
       wp[l] = TnProblem{nullptr, nullptr, nullptr, lay->out_dim[l], lay->in_dim[l]};
       all += (size_t)lay->in_dim[l] * lay->out_dim[l];
     }
-    const size_t pb = (size_t)gemm_tn_batch_splits(c.mlp_dtype, wp, L - 1, c.max_batch) * all * sizeof(float);
+    // the count of k-ranges grows with the batch, and only batches of a multiple of 32 rows take this
+    // path: the largest such batch bounds what any step needs
+    const size_t pb =
+        (size_t)gemm_tn_batch_splits(c.mlp_dtype, wp, L - 1, c.max_batch / 32 * 32) * all * sizeof(float);
     if (pb > max_partial) max_partial = pb;
   }
   lay->wgrad_partial = take(&cur, max_partial);
+  lay->wgrad_partial_bytes = max_partial;
   lay->colsum_stride = (size_t)lay->colsum_chunks * max_h;   // one buffer per hidden layer: they are reduced at the end of a step
   lay->colsum_partial = take(&cur, lay->colsum_stride * (size_t)(L > 1 ? L - 1 : 1) * sizeof(float));
   lay->emb_partial = take(&cur, embedding_partial_floats(c) * sizeof(float));
@@ -560,6 +564,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
       wp[i].partial = next;
       next += (size_t)batch_splits * wp[i].M * wp[i].N;
     }
+    if ((size_t)(next - wpart) * sizeof(float) > lay.wgrad_partial_bytes) return GEAR_ERR_CAPACITY;  // cannot happen: sized for the largest batch
     GEAR_RUN("wgrad_gemm", launch_gemm_tn_batch(wp, n_wp, B, batch_splits, status, s));
     SplitkProblem sp[GEAR_MAX_LAYERS];
     for (int i = 0; i < n_wp; ++i) {

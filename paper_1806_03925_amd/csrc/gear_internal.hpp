@@ -163,6 +163,7 @@ struct Layout {
   size_t relu_bits[GEAR_MAX_LAYERS];  // [B x out/8] sign bitmaps of the hidden activations
   size_t wc[GEAR_MAX_LAYERS], wct[GEAR_MAX_LAYERS], wgrad_partial, colsum_partial, emb_partial;
   size_t colsum_stride;              // floats between the column-sum partials of consecutive layers
+  size_t wgrad_partial_bytes;        // size of the split-K partial region
   size_t occ_view;
   struct G {
     size_t keys[2], vals[2], block_hist, tile_heads, unique, segoff, pos_seg, n_unique;

@@ -272,6 +272,20 @@ def test_three_hidden_layers(batch):
     check_state(wl, st, orc, f"three hidden layers B={batch}", fu, fl, fi)
 
 
+def test_batches_smaller_than_the_largest_take_whichever_weight_gradient_path_fits():
+    """A state sized for 1500 views (no multiple of 32 rows) steps through batches of 1472 (all weight
+    gradients in one launch, more split-K partials than a layer-by-layer step of 1500 needs), 1500 and 700."""
+    wl = get_workload("bf16").scaled(n_users=50_000, n_urls=1 << 15, n_images=5_000, M=4)
+    cfg, st, orc = make_pair(wl, max_batch=1500)
+    src = PageViewSource(wl)
+    fu, fl, fi = set(), set(), set()
+    for step, batch in enumerate((1472, 1500, 700)):
+        b = src.batch(step, batch=batch)
+        ref, fv, imgs = check_step(wl, st, orc, b, 0.05, f"max 1500, B={batch}", earlier_flipped_imgs=fi)
+        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
+    check_state(wl, st, orc, "max 1500", fu, fl, fi)
+
+
 def test_epoch_pattern_free_running():
     """One image per view, every image once per epoch: cold rows each step, groups close after M epochs."""
     wl = get_workload("epoch").scaled(batch=600, n_images=1800, M=2)
