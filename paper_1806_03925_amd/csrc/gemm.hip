@@ -404,7 +404,8 @@ template <int EPI>
 __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
                                                int wn, int lane, int M, int N, const float *__restrict__ bias,
                                                const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
-                                               uint8_t *__restrict__ relu_bits, float (&colacc)[8]) {
+                                               uint8_t *__restrict__ relu_bits, float (&colacc)[8],
+                                               const float *tile_bias, const uint32_t (&hbits)[TM][4]) {
   const int c = lane & 31, g = lane >> 5;
   const int wave_m0 = m0 + wm * WM, wave_n0 = n0 + wn * WN;
   // where this wave's columns go
@@ -462,15 +463,14 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int n = wave_n0 + j * 32 + 8 * (e / 4) + 4 * g + (e % 4);
-          bn[j][e] = n < N ? bias[n] : 0.0f;
+          // the tile's biases were staged in LDS before the main loop (zero beyond N)
+          bn[j][e] = tile_bias[wn * WN + j * 32 + 8 * (e / 4) + 4 * g + (e % 4)];
         }
     }
     // lane's 16-byte pieces: rows it*8 + lane/8 of each 32-row band, columns (lane%8)*8 .. +7
     const int prow = lane >> 3, cv = (lane & 7) * 8;
     const int n_vec = wave_n0 + cv;
     Pack16 h[EPI == EPI_MASK ? TM : 1][4];
-    uint32_t hbits[EPI == EPI_MASK_BITS ? TM : 1][4];  // eight sign bits per piece
     if constexpr (EPI == EPI_MASK) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -481,16 +481,6 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
             h[i][it].u = *reinterpret_cast<const uint4 *>(aux + (size_t)m * N + n_vec);
           else
             h[i][it].u = make_uint4(0u, 0u, 0u, 0u);
-        }
-    }
-    if constexpr (EPI == EPI_MASK_BITS) {
-      const uint8_t *bits = reinterpret_cast<const uint8_t *>(aux);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-          const int m = wave_m0 + i * 32 + it * 8 + prow;
-          hbits[i][it] = (m < M && n_vec < N) ? bits[(size_t)m * (N >> 3) + (n_vec >> 3)] : 0u;
         }
     }
 #pragma unroll
@@ -622,6 +612,30 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
     }
   }
 
+  // What the epilogue needs from global memory is requested here, so that it arrives while the
+  // products run: the tile's biases go to LDS (the barriers of the main loop make them visible), the
+  // sign bits of the lane's sixteen 16-byte pieces (eight bits each) stay in registers.
+  __shared__ float s_bias[EPI == EPI_BIAS_RELU ? DN : 1];
+  if constexpr (EPI == EPI_BIAS_RELU) {
+    if (tid < DN) s_bias[tid] = n0 + tid < N ? bias[n0 + tid] : 0.0f;
+  }
+  uint32_t hbits[TM][4];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) hbits[i][it] = 0u;
+  if constexpr (EPI == EPI_MASK_BITS) {
+    const uint8_t *bits = reinterpret_cast<const uint8_t *>(aux);
+    const int n_vec = n0 + wn * WN + (lane & 7) * 8;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int m = m0 + wm * WM + i * 32 + it * 8 + (lane >> 3);
+        if (m < M && n_vec < N) hbits[i][it] = bits[(size_t)m * (N >> 3) + (n_vec >> 3)];
+      }
+  }
+
   f32x16_v acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -640,7 +654,7 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
   block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
   bf16_t *patch = lds + wave * 32 * PATCH_LD;
   float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, relu_bits, colacc);
+  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, relu_bits, colacc, s_bias, hbits);
   if constexpr (EPI == EPI_MASK || EPI == EPI_MASK_BITS) {
     if (colpart) {
       // colpart[m-tile][n] = sum over the tile's rows of the stored values: lanes that share lane % 8
