@@ -140,6 +140,10 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
   for (int base = r0 + wave * ROUND; base < r1; base += 4 * ROUND) {
     Vec16<T> hv[kLogitRows][NV];
     float dot[kLogitRows];
+    // the label of the view this lane will evaluate, asked for together with the rows
+    const int my_view = base + gl * GROUPS + gi;
+    const bool mine = gl < kLogitRows && my_view < r1;
+    const float y = mine ? label[my_view] : 0.0f;
 #pragma unroll
     for (int u = 0; u < kLogitRows; ++u) {
       const int view = base + u * GROUPS + gi;
@@ -164,9 +168,6 @@ k_logit_loss(const T *__restrict__ h, const T *__restrict__ w, const float *__re
 #pragma unroll
     for (int u = 1; u < kLogitRows; ++u) z = gl == u ? dot[u] : z;
     z += b0;
-    const int my_view = base + gl * GROUPS + gi;
-    const bool mine = gl < kLogitRows && my_view < r1;
-    const float y = mine ? label[my_view] : 0.0f;
     const float ex = expf(-fabsf(z));
     const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
     const float dzv = (sig - y) * invB;
