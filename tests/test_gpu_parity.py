@@ -609,17 +609,22 @@ def test_same_step_twice_is_bit_identical():
         assert torch.equal(a, b)
 
 
-def test_one_stream_and_two_streams_give_the_same_bits():
+@pytest.mark.parametrize("name,batch", [
+    ("bf16", 3000),     # weight gradients layer by layer (the batch is no multiple of 32 rows)
+    ("bf16", 3008),     # all of them in one launch, joined to the helper stream only before their SGD
+    ("large", 8192),    # and dLoss/dx in two products with the embedding update beside the second
+])
+def test_one_stream_and_two_streams_give_the_same_bits(name, batch):
     """The step with every kernel on the caller's stream against the step that runs parts of itself
     on the helper stream: same launches, same order of every sum, so every output bit agrees."""
-    wl = get_workload("bf16").scaled(n_users=100_000, n_urls=1 << 16, n_images=5_000, M=4)
+    wl = get_workload(name).scaled(n_users=100_000, n_urls=1 << 16, n_images=5_000, M=4)
     outs = []
     for one in (False, True):
-        cfg, st, _ = make_pair(wl, max_batch=3000)
+        cfg, st, _ = make_pair(wl, max_batch=batch)
         st.one_stream = one
         src = PageViewSource(wl)
         for step in range(3):
-            g.gear_step(st, g.DeviceBatch.from_host(src.batch(step, batch=3000)), wl.M, 0.5)
+            g.gear_step(st, g.DeviceBatch.from_host(src.batch(step, batch=batch)), wl.M, 0.5)
         torch.cuda.synchronize()
         assert int(st.status.item()) == 0
         n = int(st.n_ready.item())
