@@ -233,9 +233,8 @@ class GearOracle:
         m = round_f32(a.beta1 * m + (1.0 - a.beta1) * g)
         v = round_f32(a.beta2 * v + (1.0 - a.beta2) * g * g)
         a.moments[key] = (m, v)
-        step = float(np.float32(lr / (1.0 - a.beta1 ** a.t)))
-        inv_bc2 = float(np.float32(1.0 / np.sqrt(1.0 - a.beta2 ** a.t)))
-        return w - step * m / (np.sqrt(v) * inv_bc2 + a.eps)
+        step = lr / (1.0 - a.beta1 ** a.t)
+        return w - step * m / (np.sqrt(v) / np.sqrt(1.0 - a.beta2 ** a.t) + a.eps)
 
     # ---- expiry of cached inference results (Section 1, second point; Section 3; Table 2) ------
     def expired(self, image_ids: Sequence[int], now: int, expiry: int) -> List[int]:

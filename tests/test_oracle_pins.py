@@ -92,6 +92,44 @@ def test_hand_computed_step(worked, name):
         assert np.array_equal(o.residual(int(k)), np.array(v))
 
 
+@pytest.mark.parametrize("name", ["bf16_hidden_activation_rounds", "bf16_hidden_delta_rounds"])
+def test_hand_computed_bf16_roundings_inside_the_network(worked, name):
+    """Section 3 step 4 with bf16 operands: hidden activations and hidden deltas are stored in bf16
+    before they are operands again.  Both examples are built so that the value to be stored is not a
+    bf16 number and so that, with the rounding, the logit is exactly 0 and every gradient is exact."""
+    ex = worked[name]
+    exp = ex["expect"]
+    d, D = ex["emb_dim"], ex["dfv_dim"]
+    prec = Precision("f32", "f32", "bf16", "f32")
+    mlp = [(np.array(W), np.array(b)) for W, b in zip(ex["W"], ex["b"])]
+    o = GearOracle(RowStore(len(ex["user_emb"]), d, prec.emb, dense=np.array(ex["user_emb"])),
+                   RowStore(len(ex["url_emb"]), d, prec.emb, dense=np.array(ex["url_emb"])),
+                   RowStore(len(ex["dfv"]), D, prec.dfv, dense=np.array(ex["dfv"])), mlp, ex["M"], prec)
+    v = ex["views"]
+    batch = batch_from_lists([w["user"] for w in v], [w["url"] for w in v], [w["images"] for w in v],
+                             [w["label"] for w in v])
+    r = o.step(batch, ex["lr"])
+    assert np.array_equal(r.x, np.array(exp["x"]))
+    assert np.array_equal(r.logits, np.array(exp["logits"]))
+    assert r.loss == pytest.approx(math.log(2.0), rel=1e-15)
+    for l in range(len(mlp)):
+        assert np.array_equal(r.grads[l][0], np.array(exp["dW"][l])), l
+        assert np.array_equal(r.grads[l][1], np.array(exp["db"][l])), l
+    assert np.array_equal(r.dx, np.array(exp["dx"]))
+    assert np.array_equal(r.occ_grads, np.array(exp["occ_grads"]))
+    assert r.ready_ids.tolist() == exp["ready_ids"] and np.array_equal(r.ready_grads, np.array(exp["ready_grads"]))
+    # the same data without any rounding gives the other value the derivation names: the examples do
+    # tell the two apart
+    e = GearOracle(RowStore(len(ex["user_emb"]), d, "f64", dense=np.array(ex["user_emb"])),
+                   RowStore(len(ex["url_emb"]), d, "f64", dense=np.array(ex["url_emb"])),
+                   RowStore(len(ex["dfv"]), D, "f64", dense=np.array(ex["dfv"])), mlp, ex["M"], Precision.exact())
+    q = e.step(batch, ex["lr"])
+    if "logit_without_rounding" in exp:
+        assert q.logits[0] == exp["logit_without_rounding"] and q.loss != r.loss
+    if "dx0_without_rounding" in exp:
+        assert q.dx[0, 0] == exp["dx0_without_rounding"]
+
+
 def _bare_store(M):
     z = RowStore(1, 1, "f64")
     return GearOracle(z, z, RowStore(1, 1, "f64"), [(np.zeros((1, 3)), np.zeros(1))], M, Precision.exact())
