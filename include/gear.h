@@ -17,9 +17,13 @@
  * forked from and joined back into the caller's stream).  Calls enqueue their
  * kernels on the given hipStream_t (passed as void*) and return without
  * synchronising.  Results are valid once the caller has synchronised that
- * stream.  The stream must belong to the current device.  Steps on one device
- * must not overlap each other; the entry points may be called from several
- * host threads (one per device, say).
+ * stream.  The stream must belong to the current device.  The entry points may
+ * be called from several host threads; steps issued on one device are enqueued
+ * one after the other (a per-device lock is held while a step enqueues) and
+ * share the helper stream, so they run in the order they were issued.  Each
+ * step needs a workspace of its own while it is in flight.  If a call returns
+ * GEAR_ERR_HIP part-way through its enqueue, whatever it had put on the helper
+ * stream is still joined back into the caller's stream before it returns.
  *
  * Errors.  Everything the host can check (NULL pointers, dimensions, M < 1,
  * sizes over the configured maxima, a workspace that is too small) is reported
@@ -95,7 +99,7 @@ typedef struct gear_batch {
 /* Outputs of one step (device memory, caller-owned). */
 typedef struct gear_step_out {
   float *loss;            /* [1] mean sigmoid cross-entropy of the batch                         */
-  int32_t *n_ready;       /* [1] number of emitted averages                                      */
+  int32_t *n_ready;       /* [1] number of emitted averages (0 when status is not 0)             */
   int32_t *ready_ids;     /* [ready_cap] image ids, ascending; an image that completed several
                              groups of M in this step appears once per group, oldest first       */
   float *ready_grads;     /* [ready_cap x dfv_dim] fp32, row r = average for ready_ids[r]        */
@@ -126,7 +130,8 @@ int64_t gear_mlp_param_offset(const gear_config *cfg, int32_t layer, int32_t whi
 /* Byte offset and size, inside the workspace, of an intermediate of the last gear_step, for
  * inspection by tests: "x" [max_batch x F] mlp_dtype, "logits" [max_batch] f32, and dLoss/dx in two
  * pieces: "dx_emb" [max_batch x 2*emb_dim] f32 (user and URL slots) and "dx_dfv" [max_batch x dfv_dim]
- * in mlp_dtype (the DFV slot).
+ * in mlp_dtype (the DFV slot), and "h0", "h1", ... [max_batch x layer_out[l]] mlp_dtype, the stored
+ * activations of the hidden layers (zero where the unit is off).
  * Returns GEAR_ERR_INVALID for an unknown name. */
 gear_status gear_workspace_region(const gear_config *cfg, const char *name, size_t *offset, size_t *bytes);
 
@@ -297,6 +302,14 @@ gear_profile *gear_profile_create(void);
 void gear_profile_destroy(gear_profile *p);
 int32_t gear_profile_count(const gear_profile *p);
 gear_status gear_profile_span(const gear_profile *p, int32_t i, const char **name, float *ms);
+
+/* Test hooks for the error paths of a step (no device needs to fail for them to be walked).
+ * gear_debug_fail_launch(n): on the calling thread, the n-th kernel launch counted from now (n >= 1)
+ * is not enqueued and the step returns GEAR_ERR_HIP there, leaving caller state half-updated as any
+ * failed launch would; 0 switches it off.  gear_debug_helper_idle(): 1 if the current device's helper
+ * stream has nothing left to run (or was never created), 0 if it is still busy, -1 on a HIP error. */
+void gear_debug_fail_launch(int32_t nth);
+int32_t gear_debug_helper_idle(void);
 
 const char *gear_status_string(gear_status s);
 

@@ -125,6 +125,13 @@ class StepResult:
     grads: List[Tuple[np.ndarray, np.ndarray]]       # (dW_l, db_l)
     occ_grads: np.ndarray          # [nnz x D] dLoss/dDFV per occurrence, flat CSR order
     kink_margin: np.ndarray        # [B x hidden layers] min over the layer's units of |a| / max|a|
+    dx_own: Optional[np.ndarray] = None   # dLoss/dx with every ReLU decided by this oracle's own arithmetic (= dx unless relu_choice changed a unit)
+    near_units: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int64))     # [B] hidden units within kink_tol of the kink
+    active_units: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int64))   # [B] active units of the view's sparsest hidden layer
+    chosen_units: int = 0          # near-kink units whose branch was taken from relu_choice against the own decision
+    chosen_per_view: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int64))   # [B] the same, per view
+    refused_units: int = 0         # units where relu_choice disagreed but the pre-activation is not near the kink (own decision kept)
+    emb_term_scale: Dict = field(default_factory=dict)   # ("user"|"url", id) -> largest |element| of the gradient terms summed into the row
     ready_term_scale: np.ndarray = field(default_factory=lambda: np.zeros(0))   # [n_ready] largest |element| of the M gradients behind each average
     user_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
     url_unique: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))
@@ -281,7 +288,60 @@ class GearOracle:
         return total / self.M
 
     # ---- one training step -------------------------------------------------------------------
-    def step(self, batch, lr: float) -> StepResult:
+    def _forward_backward(self, x: np.ndarray, y: np.ndarray, relu_choice, kink_tol: float) -> dict:
+        """Forward to the loss and backward to dLoss/dx from the current (pre-step) parameters; changes no
+        state.  relu_choice (one boolean [B x H_l] array per hidden layer, or None): for units whose
+        pre-activation lies within kink_tol * max|a_l| of zero, the branch to take instead of this
+        arithmetic's own `a > 0`; everywhere else the own decision stands whatever relu_choice says."""
+        B = x.shape[0]
+        L = len(self.mlp)
+        Wc = [round_to(W, self.prec.mlp) for W, _ in self.mlp]
+        h = [x]
+        active = [None]                                              # ReLU'(a_l): 1 where a_l > 0
+        kink = np.full((B, max(L - 1, 1)), np.inf)
+        near_units = np.zeros(B, dtype=np.int64)
+        active_units = np.full(B, np.iinfo(np.int64).max, dtype=np.int64)
+        chosen = refused = 0
+        chosen_per_view = np.zeros(B, dtype=np.int64)
+        for l in range(L - 1):
+            a = h[l] @ Wc[l].T + self.mlp[l][1]
+            scale = np.maximum(np.abs(a).max(axis=1), np.finfo(np.float64).tiny)
+            kink[:, l] = np.abs(a).min(axis=1) / scale
+            on = a > 0
+            near = np.abs(a) < kink_tol * scale[:, None]
+            near_units += near.sum(axis=1)
+            if relu_choice is not None:
+                want = np.asarray(relu_choice[l], dtype=bool)
+                differs = want != on
+                chosen += int((differs & near).sum())
+                chosen_per_view += (differs & near).sum(axis=1)
+                refused += int((differs & ~near).sum())
+                on = np.where(near, want, on)
+            active_units = np.minimum(active_units, on.sum(axis=1))
+            active.append(on)
+            h.append(round_to(np.where(on, np.maximum(a, 0.0), 0.0), self.prec.mlp))
+        z = (h[L - 1] @ Wc[L - 1].T + self.mlp[L - 1][1])[:, 0]
+        loss = float(np.sum(bce_with_logits(z, y)) / B) if B else 0.0
+
+        delta = ((sigmoid(z) - y) / max(B, 1)).reshape(B, 1)       # dLoss/dz, mean reduction
+        grads: List[Tuple[np.ndarray, np.ndarray]] = [None] * L     # type: ignore
+        dx = np.zeros_like(x)
+        for l in range(L - 1, -1, -1):
+            grads[l] = (delta.T @ h[l], delta.sum(axis=0))
+            back = delta @ Wc[l]
+            if l > 0:
+                # hidden deltas are MLP operands: ReLU mask, then operand rounding
+                delta = round_to(np.where(active[l], back, 0.0), self.prec.mlp)
+            else:
+                # dLoss/dx is never an operand of a contraction again: it stays unrounded
+                dx = back
+        return dict(z=z, loss=loss, grads=grads, dx=dx, kink=kink, near_units=near_units,
+                    active_units=active_units, chosen=chosen, refused=refused, chosen_per_view=chosen_per_view)
+
+    def step(self, batch, lr: float, relu_choice=None, kink_tol: float = 0.0) -> StepResult:
+        """One step.  relu_choice / kink_tol: see _forward_backward; with them the step follows the given
+        branch at hidden units that are within rounding distance of the ReLU kink (a comparison with
+        another arithmetic then does not hinge on which side of zero each landed), and only there."""
         B, d, D, F, M = batch.B, self.d, self.D, self.F, self.M
         user_id, url_id = batch.user_id, batch.url_id
         off, img_id, y = batch.img_off, batch.img_id, batch.label.astype(np.float64)
@@ -304,38 +364,18 @@ class GearOracle:
                 x[b, 2 * d:] = pooled / n_b
         x = round_to(x, self.prec.mlp)
 
-        # 2. Forward through the Sparse Part to the loss (Section 3, step 4).
-        L = len(self.mlp)
-        Wc = [round_to(W, self.prec.mlp) for W, _ in self.mlp]
-        h = [x]
-        active = [None]                                              # ReLU'(a_l): 1 where a_l > 0
-        kink = np.full((B, max(L - 1, 1)), np.inf)
-        for l in range(L - 1):
-            a = h[l] @ Wc[l].T + self.mlp[l][1]
-            scale = np.maximum(np.abs(a).max(axis=1), np.finfo(np.float64).tiny)
-            kink[:, l] = np.abs(a).min(axis=1) / scale
-            active.append(a > 0)
-            h.append(round_to(np.where(a > 0, a, 0.0), self.prec.mlp))
-        z = (h[L - 1] @ Wc[L - 1].T + self.mlp[L - 1][1])[:, 0]
-        loss = float(np.sum(bce_with_logits(z, y)) / B) if B else 0.0
-
-        # 3. Back-propagation through the Sparse Part only, from pre-step parameters.
-        delta = ((sigmoid(z) - y) / max(B, 1)).reshape(B, 1)       # dLoss/dz, mean reduction
-        grads: List[Tuple[np.ndarray, np.ndarray]] = [None] * L     # type: ignore
-        for l in range(L - 1, -1, -1):
-            grads[l] = (delta.T @ h[l], delta.sum(axis=0))
-            back = delta @ Wc[l]
-            if l > 0:
-                # hidden deltas are MLP operands: ReLU mask, then operand rounding
-                delta = round_to(np.where(active[l], back, 0.0), self.prec.mlp)
-            else:
-                # dLoss/dx is never an operand of a contraction again: it stays unrounded
-                dx = back
+        # 2.-3. Forward to the loss and back-propagation through the Sparse Part only (Section 3, step 4).
+        own = self._forward_backward(x, y, None, kink_tol)
+        fb = own
+        if relu_choice is not None:
+            fb = self._forward_backward(x, y, relu_choice, kink_tol)
+        z, loss, grads, dx, kink = fb["z"], fb["loss"], fb["grads"], fb["dx"], fb["kink"]
 
         # 4. Apply the Sparse Part's gradients: plain SGD, or Adam when `self.adam` is set (MLP: every
         #    element; tables: the touched rows only, moments included).
         if self.adam is not None:
             self.adam.t += 1
+        emb_term_scale: Dict = {}
         new_mlp = []
         for l, ((W, b), (dW, db)) in enumerate(zip(self.mlp, grads)):
             new_mlp.append((round_to(self._update(("W", l), W, dW, lr), self.prec.master),
@@ -346,6 +386,7 @@ class GearOracle:
             for b in range(B):                                       # batch order
                 k = int(ids[b])
                 row_grad[k] = row_grad.get(k, np.zeros(d)) + dx[b, lo:lo + d]
+                emb_term_scale[(name, k)] = max(emb_term_scale.get((name, k), 0.0), float(np.abs(dx[b, lo:lo + d]).max()))
             for k, g in row_grad.items():
                 table.set_row(k, self._update((name, k), table.row(k), g, lr))
 
@@ -369,7 +410,10 @@ class GearOracle:
 
         iu, isegoff, iperm = stable_groups(img_id)
         return StepResult(loss=loss, ready_ids=ready_ids, ready_grads=ready_grads, x=x, logits=z,
-                          dx=dx, grads=grads, occ_grads=occ, kink_margin=kink,
+                          dx=dx, grads=grads, occ_grads=occ, kink_margin=kink, dx_own=own["dx"],
+                          near_units=own["near_units"], active_units=own["active_units"],
+                          chosen_units=fb["chosen"], refused_units=fb["refused"], chosen_per_view=fb["chosen_per_view"],
+                          emb_term_scale=emb_term_scale,
                           user_unique=stable_groups(user_id)[0], url_unique=stable_groups(url_id)[0],
                           img_unique=iu, img_segoff=isegoff, img_perm=iperm,
                           ready_term_scale=np.asarray([term_scale[e] for e in order], dtype=np.float64))

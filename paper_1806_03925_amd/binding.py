@@ -27,7 +27,7 @@ EXPORTS = (
     "gear_refresh_dfv_n", "gear_stamp_dfv_n",
     "gear_dense_workspace_bytes", "gear_dense_infer", "gear_dense_backward", "gear_dense_backward_n", "gear_group_ids",
     "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
-    "gear_status_string",
+    "gear_debug_fail_launch", "gear_debug_helper_idle", "gear_status_string",
 )
 
 
@@ -135,6 +135,10 @@ def _load() -> C.CDLL:
     lib.gear_profile_count.argtypes = [C.c_void_p]
     lib.gear_profile_span.restype = C.c_int
     lib.gear_profile_span.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_float)]
+    lib.gear_debug_fail_launch.restype = None
+    lib.gear_debug_fail_launch.argtypes = [C.c_int32]
+    lib.gear_debug_helper_idle.restype = C.c_int32
+    lib.gear_debug_helper_idle.argtypes = []
     lib.gear_status_string.restype = C.c_char_p
     lib.gear_status_string.argtypes = [C.c_int]
     return lib
@@ -192,6 +196,14 @@ def gear_workspace_region(cfg: gear_config, name: str):
     _check(lib.gear_workspace_region(C.byref(cfg), name.encode(), C.byref(off), C.byref(size)),
            "gear_workspace_region")
     return off.value, size.value
+
+
+def gear_debug_fail_launch(nth: int) -> None:
+    lib.gear_debug_fail_launch(int(nth))
+
+
+def gear_debug_helper_idle() -> int:
+    return int(lib.gear_debug_helper_idle())
 
 
 def gear_fill_normal(dst: torch.Tensor, n_rows: int, dim: int, seed: int, stream_id: int, std: float) -> None:
@@ -287,6 +299,9 @@ class GearState:
             return raw.view(torch.float32)[:B * 2 * d].view(B, 2 * d)
         if name == "dx_dfv":
             return raw.view(TORCH_DTYPE[self.cfg.mlp_dtype])[:B * D].view(B, D)
+        if name[0] == "h":
+            H = self.cfg.layer_out[int(name[1:])]
+            return raw.view(TORCH_DTYPE[self.cfg.mlp_dtype])[:B * H].view(B, H)
         return raw.view(torch.float32)[:B]
 
 

@@ -203,6 +203,7 @@ struct SideLane {
   hipStream_t stream = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
   bool ready = false;
+  std::mutex busy;  // held while a step enqueues: two host threads never interleave their forks and joins
 };
 SideLane g_side[64];
 std::mutex g_side_mutex;
@@ -219,22 +220,74 @@ SideLane *side_lane() {
   std::lock_guard<std::mutex> lock(g_side_mutex);
   SideLane &l = g_side[dev];
   if (!l.ready) {
-    SideLane made;
-    bool ok = hipStreamCreateWithFlags(&made.stream, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&made.fork, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&made.join, hipEventDisableTiming) == hipSuccess;
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&join, hipEventDisableTiming) == hipSuccess;
     if (!ok) {
-      if (made.join) (void)hipEventDestroy(made.join);
-      if (made.fork) (void)hipEventDestroy(made.fork);
-      if (made.stream) (void)hipStreamDestroy(made.stream);
+      if (join) (void)hipEventDestroy(join);
+      if (fork) (void)hipEventDestroy(fork);
+      if (stream) (void)hipStreamDestroy(stream);
       return nullptr;
     }
-    made.ready = true;
-    l = made;
+    l.stream = stream;
+    l.fork = fork;
+    l.join = join;
+    l.ready = true;
   }
   return &l;
 }
+
+// A step's use of the helper lane.  Holds the lane for the whole enqueue, so that steps issued from
+// several host threads on one device use the lane's two events one after the other, and makes sure
+// that whatever was forked to the helper stream is joined back into the caller's stream however the
+// enqueue ends: after an early return (a failed launch) the next call on the caller's stream must
+// not run beside kernels this call left on the helper stream.
+class LaneScope {
+ public:
+  LaneScope(SideLane *side, hipStream_t caller) : side_(side), s_(caller) {
+    if (side_) side_->busy.lock();
+  }
+  ~LaneScope() {
+    if (!side_) return;
+    if (forked_ && !joined_) {
+      if (hipEventRecord(side_->join, side_->stream) == hipSuccess) (void)hipStreamWaitEvent(s_, side_->join, 0);
+    }
+    side_->busy.unlock();
+  }
+  LaneScope(const LaneScope &) = delete;
+  LaneScope &operator=(const LaneScope &) = delete;
+  // what the caller's stream has done so far happens before whatever the helper stream is given next
+  hipError_t fork() {
+    if (!side_) return hipSuccess;
+    hipError_t e = hipEventRecord(side_->fork, s_);
+    if (e != hipSuccess) return e;
+    forked_ = true;
+    joined_ = false;
+    return hipStreamWaitEvent(side_->stream, side_->fork, 0);
+  }
+  // marks the point of the helper stream that a later wait() refers to
+  hipError_t mark() { return side_ ? hipEventRecord(side_->join, side_->stream) : hipSuccess; }
+  // the caller's stream continues after the last mark(); final = nothing is given to the helper after it
+  hipError_t wait(bool final) {
+    if (!side_) return hipSuccess;
+    hipError_t e = hipStreamWaitEvent(s_, side_->join, 0);
+    if (e == hipSuccess && final) joined_ = true;
+    return e;
+  }
+
+ private:
+  SideLane *side_;
+  hipStream_t s_;
+  bool forked_ = false, joined_ = false;
+};
 }  // namespace
+
+// Test hook: the n-th launch of this thread's next steps reports failure instead of being enqueued
+// (0 = off).  Lets a test walk the error paths of a step without a failing device.
+thread_local int g_fail_at = 0;
+inline bool fail_injected() { return g_fail_at > 0 && --g_fail_at == 0; }
 
 #define GEAR_HIP(expr)                             \
   do {                                             \
@@ -243,6 +296,7 @@ SideLane *side_lane() {
 // a launch bracketed by profile events (when a profile is attached)
 #define GEAR_RUN(name, expr)    \
   do {                          \
+    if (fail_injected()) return GEAR_ERR_HIP; \
     Span span_(prof, name, s);  \
     GEAR_HIP(expr);             \
   } while (0)
@@ -283,6 +337,11 @@ gear_status gear_workspace_region(const gear_config *cfg, const char *name, size
   } else if (!strcmp(name, "dx_dfv")) {
     *offset = lay.dx_dfv;
     *bytes = B * cfg->dfv_dim * lay.act_bytes;
+  } else if (name[0] == 'h' && name[1] >= '0' && name[1] < '0' + GEAR_MAX_LAYERS && !name[2] &&
+             name[1] - '0' < lay.L - 1) {
+    const int l = name[1] - '0';
+    *offset = lay.h[l];
+    *bytes = B * lay.out_dim[l] * lay.act_bytes;
   } else {
     return GEAR_ERR_INVALID;
   }
@@ -407,10 +466,8 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   SideLane *side = one_stream ? nullptr : side_lane();
   if (!one_stream && !side) return GEAR_ERR_HIP;
   hipStream_t helper = one_stream ? s : side->stream;
-  if (side) {
-    GEAR_HIP(hipEventRecord(side->fork, s));
-    GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
-  }
+  LaneScope lane(side, s);
+  GEAR_HIP(lane.fork());
   {
     // operand copies of the weights (all layers in one launch), ahead of the gather on the caller's
     // stream: the first product then needs no event, and behind the gather's many workgroups the
@@ -432,7 +489,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                              out->n_ready, status, s));
     GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
   }
-  if (side) GEAR_HIP(hipEventRecord(side->join, side->stream));
+  GEAR_HIP(lane.mark());
 
   // forward
   void *x = ws + lay.x;
@@ -459,7 +516,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   // and need not know whether the ids were in range or the ready list fits.  With one launch for
   // all weight gradients that kernel is the last one of the step, behind the final join; otherwise
   // the stream waits here for the helper's first part, so that the status word is final.
-  if (side && batch_splits == 0) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));
+  if (batch_splits == 0) GEAR_HIP(lane.wait(false));
   GEAR_RUN("logit_loss", launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1],
                                            b->label, B, lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2],
                                            (float *)(ws + lay.loss_partial), status, s));
@@ -513,10 +570,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
       if ((double)B * (F - E2) * lay.out_dim[0] >= kSplitDxMacs) {
         GEAR_RUN("dgrad_gemm_emb", launch_gemm_nt(dt, ws + lay.delta[0], ws + lay.wct[0], B, E2, lay.out_dim[0], EPI_DX,
                                                   nullptr, dx_dfv, dx_emb, E2, nullptr, nullptr, status, s));
-        if (side) {
-          GEAR_HIP(hipEventRecord(side->fork, s));
-          GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
-        }
+        GEAR_HIP(lane.fork());
         {
           hipStream_t s = helper;
           if (gear_status st = small_reductions(s)) return st;
@@ -540,10 +594,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
   // launched first and, where they can, as one launch of at most one round of workgroups, so that
   // they hold their CUs before the bookkeeping's many small workgroups arrive and fill what is
   // left; a product arriving later would wait until all of those have been placed.
-  if (side) {
-    GEAR_HIP(hipEventRecord(side->fork, s));
-    GEAR_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
-  }
+  GEAR_HIP(lane.fork());
   {
     hipStream_t s = helper;
     if (!embedding_updated) {
@@ -555,7 +606,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     GEAR_RUN("accumulate", launch_accumulate(*cfg, gb.p[2], plan, dx_dfv, grad_accum, M, out->ready_ids,
                                              out->ready_grads, status, s));
   }
-  if (side) GEAR_HIP(hipEventRecord(side->join, side->stream));
+  GEAR_HIP(lane.mark());
   // SGD on the hidden layers' weights: split-K wgrad (the logit layer and all biases are done on the helper stream)
   bool joined = false;
   if (batch_splits > 0) {
@@ -574,7 +625,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     }
     // the step's work on the helper stream ends here; the sums of the partials and the SGD follow it
     // (they would not get onto the device before the bookkeeping's workgroups are all placed anyway)
-    if (side) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));
+    GEAR_HIP(lane.wait(true));
     joined = true;
     GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
   } else {
@@ -587,7 +638,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                                status, s));
     }
   }
-  if (side && !joined) GEAR_HIP(hipStreamWaitEvent(s, side->join, 0));  // the step ends on the caller's stream
+  if (!joined) GEAR_HIP(lane.wait(true));  // the step ends on the caller's stream
   if (out->dbg_img_unique && b->nnz > 0)
     GEAR_HIP(hipMemcpyAsync(out->dbg_img_unique, gb.p[2].unique, (size_t)b->nnz * 4, hipMemcpyDeviceToDevice, s));
   if (out->dbg_img_segoff)
@@ -703,6 +754,17 @@ gear_status gear_gemm(int32_t dtype, int32_t form, const void *A, const void *B,
     return GEAR_ERR_INVALID;
   }
   return GEAR_OK;
+}
+
+void gear_debug_fail_launch(int32_t nth) { g_fail_at = nth > 0 ? nth : 0; }
+
+int32_t gear_debug_helper_idle(void) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  if (!g_side[dev].ready) return 1;
+  const hipError_t e = hipStreamQuery(g_side[dev].stream);
+  return e == hipSuccess ? 1 : (e == hipErrorNotReady ? 0 : -1);
 }
 
 gear_profile *gear_profile_create(void) {

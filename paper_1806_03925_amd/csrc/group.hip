@@ -377,8 +377,10 @@ __global__ void __launch_bounds__(kSortBlock) k_plan_scatter(GroupProblem p, Acc
   }
   if (tile0 + kSortTile >= p.n && threadIdx.x == 0) {
     *plan.n_units = base_u + tu;
-    *n_ready = base_e + te;
-    if (base_e + te > ready_cap) atomicCAS(status, 0, GEAR_ERR_CAPACITY);
+    // a list that does not fit is reported as empty: nobody may read ready_ids past ready_cap
+    const bool over = base_e + te > ready_cap;
+    *n_ready = over ? 0 : base_e + te;
+    if (over) atomicCAS(status, 0, GEAR_ERR_CAPACITY);
   }
 }
 

@@ -5,6 +5,7 @@ Integer results are compared bit for bit, floating point by the row rule of orac
 initialiser and run freely; nothing the oracle consumes comes from the GPU.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -13,7 +14,7 @@ import torch
 from gear_inputs import PageViewSource, get_workload
 from gear_inputs.pageviews import PageViewBatch, batch_from_lists
 from oracle import philox_normal
-from oracle.compare import REL, assert_rows_close, row_errors
+from oracle.compare import REL, assert_delta_rows_close, assert_rows_close, row_errors
 from oracle.from_workload import oracle_for
 from oracle.gear_oracle import stable_groups
 from oracle.rounding import round_to
@@ -44,99 +45,187 @@ def make_pair(wl, max_batch=None, ready_cap=None):
     return cfg, st, oracle_for(wl)
 
 
-def check_step(wl, st, orc, batch: PageViewBatch, lr: float, what: str, adam=None, flip_cap=None,
-               earlier_flipped_imgs=()):
-    """Run one step on both sides and compare every output; returns the oracle's result."""
-    rel = REL[wl.mlp_dtype]
-    dev = g.DeviceBatch.from_host(batch)
-    if adam is None:
-        g.gear_step(st, dev, wl.M, lr)
-    else:
-        g.gear_step_adam(st, dev, wl.M, lr, adam)
-    torch.cuda.synchronize()
-    ref = orc.step(batch, float(np.float32(lr)))
-    B, d = batch.B, wl.emb_dim
-    assert int(st.status.item()) == 0, what
-
-    # grouping of the image ids
-    nu = int(st.dbg[3].item())
-    assert nu == len(ref.img_unique), what
-    assert np.array_equal(st.dbg[0][:nu].cpu().numpy(), ref.img_unique), what
-    assert np.array_equal(st.dbg[1][:nu + 1].cpu().numpy(), ref.img_segoff), what
-    assert np.array_equal(st.dbg[2][:batch.nnz].cpu().numpy(), ref.img_perm), what
-
-    # forward
-    assert_rows_close(f64(st.region("x", B)), ref.x, rel, f"{what}: x")
-    assert_rows_close(f64(st.region("logits", B)), ref.logits, rel, f"{what}: logits")
-    assert abs(float(st.loss.item()) - ref.loss) <= rel * abs(ref.loss), (what, st.loss.item(), ref.loss)
-
-    # dLoss/dx.  A view whose hidden pre-activation lies within rounding distance of the ReLU kink
-    # may take the other branch, which moves its whole row by about 1/sqrt(active units).  In fp32
-    # the two sides differ by accumulation order only (~1e-6 of the layer's scale).  With bf16
-    # operands an element of x or h can round to the neighbouring bf16 value (2^-8 relative), which
-    # shifts the next layer's pre-activations by about 2^-8 * |w| / sqrt(fan_in) ~ 1e-3 of their
-    # scale.  Rows outside that distance must pass; inside it they may flip, but only a few do.
-    tol = 1e-5 if wl.mlp_dtype == "f32" else 2e-3
-    near_kink = (ref.kink_margin < tol).any(axis=1)
-    dx = f64(st.region("dx", B))
-    assert np.isfinite(dx).all()
-    err, scale = row_errors(dx, ref.dx)
-    failed = err > rel * scale
-    assert not (failed & ~near_kink).any(), \
-        f"{what}: dx rows off away from any kink: {np.flatnonzero(failed & ~near_kink)[:5]}"
-    cap = max(2, 0.002 * B) if wl.mlp_dtype == "f32" else max(2, 0.06 * B)
-    if flip_cap is not None:
-        cap = max(2, flip_cap * B)
-    assert failed.sum() <= cap, f"{what}: {failed.sum()} of {B} dx rows flipped at kinks ({near_kink.sum()} rows are near one)"
-    assert np.median(err / scale) <= rel / 4, f"{what}: median dx row error {np.median(err / scale):.2e}"
-    # downstream sums inherit a view's error: views at more than half the bar (far above the rounding
-    # noise of a view with no flipped unit) are treated like the failed ones when rows are exempted
-    flipped_views = np.flatnonzero(err > 0.5 * rel * scale)
-    flipped_imgs = set()
-    for b in flipped_views:
-        flipped_imgs.update(batch.img_id[batch.img_off[b]:batch.img_off[b + 1]].tolist())
-
-    # ready list and averaged gradients
-    n_ready = int(st.n_ready.item())
-    assert n_ready == len(ref.ready_ids), what
-    assert np.array_equal(st.ready_ids[:n_ready].cpu().numpy(), ref.ready_ids), what
-    if n_ready:
-        # an average can also hold gradients that flipped views of earlier steps left in the accumulator
-        ex = np.isin(ref.ready_ids, list(flipped_imgs | set(earlier_flipped_imgs)))
-        assert_rows_close(f64(st.ready_grads[:n_ready]), ref.ready_grads, rel, f"{what}: ready_grads", exempt=ex,
-                          term_scale=ref.ready_term_scale)
-    return ref, flipped_views, flipped_imgs
+# A hidden unit whose pre-activation is within this fraction of its layer's largest one may land on
+# either side of the ReLU kink: fp32 products summed in another order differ by about 1e-6 of the
+# layer's scale; with bf16 operands an element of x or h can round to the neighbouring bf16 value
+# (2^-8 relative), which shifts the next layer's pre-activations by about 1e-3 of their scale.
+KINK_TOL = {"f32": 1e-5, "bf16": 2e-3}
+# A unit taking the other branch moves a view's dLoss/dx row by about 1/sqrt(active units) of its scale;
+# a row compared with the oracle's own decisions may be off by this multiple of (units of the view
+# that took the other branch) / sqrt(active units), and no more.
+KINK_C = 4.0
+STATS = []          # one line per comparison: how close to the bars and caps each test runs
 
 
-def check_state(wl, st, orc, what, flipped_users=(), flipped_urls=(), flipped_imgs=()):
-    """Compare the persistent state: counters bit-exact, accumulators and tables by rows."""
-    rel = REL[wl.mlp_dtype]
-    counts = st.counts.cpu().numpy()
-    touched = np.array(sorted(orc.counts), dtype=np.int64)
-    assert int(counts.sum()) == sum(orc.counts.values()), what
-    assert np.array_equal(counts[touched], np.array([orc.counts[i] for i in touched], dtype=np.int32)), what
-    if len(touched):
-        acc = f64(st.grad_accum[torch.from_numpy(touched).cuda()])
-        ref = np.stack([orc.residual(i) for i in touched])
-        # images whose count is a multiple of M hold exactly zero
-        full = np.array([orc.counts[i] % wl.M == 0 for i in touched])
-        assert not acc[full].any(), what
-        assert_rows_close(acc, ref, rel, f"{what}: grad_accum", exempt=np.isin(touched, list(flipped_imgs)),
-                          term_scale=[orc.residual_term_scale(i) for i in touched])
-    # untouched accumulators are still zero
-    nz_rows = int((st.grad_accum != 0).any(dim=1).sum().item())
-    assert nz_rows <= len(touched), what
-    for name, table, store, flipped in (("user_emb", st.user_emb, orc.user_emb, flipped_users),
-                                        ("url_emb", st.url_emb, orc.url_emb, flipped_urls)):
-        ids = np.array(sorted(store._rows), dtype=np.int64)
-        if len(ids):
-            got = f64(table[torch.from_numpy(ids).cuda()])
-            assert_rows_close(got, np.stack([store.row(i) for i in ids]), rel, f"{what}: {name}",
-                              exempt=np.isin(ids, list(flipped)))
-    for l, (W, b) in enumerate(orc.mlp):
-        Wg, bg = st.layer_params(l)
-        assert_rows_close(f64(Wg), W, rel, f"{what}: W{l}")
-        assert_rows_close(f64(bg), b, rel, f"{what}: b{l}")
+def note(line):
+    STATS.append(line)
+    print("[parity] " + line, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _stats_file():
+    yield
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if STATS and os.path.isdir(out):
+        with open(os.path.join(out, "parity_margins.txt"), "w") as f:
+            f.write("\n".join(STATS) + "\n")
+
+
+class Pair:
+    """The HIP path and the oracle side by side, both from their own initial state, free-running.
+
+    Every step is compared twice.  (1) Against the oracle's own ReLU decisions: dLoss/dx rows of views
+    with no hidden unit near the kink must pass the row rule; the others may differ, by at most
+    KINK_C * (units on the other branch) / sqrt(active units) of the row's scale, and only a capped
+    number of them do.  (2) Against
+    the oracle taking, at near-kink units only, the branch the kernels took (read from the stored
+    activations): then every output and every touched row of the state must pass the row rule, with no
+    exemption.  The oracle checks the distance to the kink itself and refuses a branch elsewhere; a
+    refusal fails the test.  The oracle's state advances with (2), so both sides stay on the same
+    branches over many steps."""
+
+    def __init__(self, wl, max_batch=None, ready_cap=None, adam_eps=None):
+        self.wl = wl
+        self.cfg, self.st, self.orc = make_pair(wl, max_batch=max_batch, ready_cap=ready_cap)
+        self.rel = REL[wl.mlp_dtype]
+        self.kink_tol = KINK_TOL[wl.mlp_dtype]
+        self.adam = None
+        if adam_eps is not None:
+            self.orc.use_adam(eps=adam_eps)
+            self.adam = g.AdamMoments(self.st, eps=adam_eps)
+        self.steps = 0
+        self.term = {}                                   # (table, id) -> largest |lr * gradient term| summed into the row
+        self.before = {"user": {}, "url": {}}            # id -> (kernel's row, oracle's row) before their first touch
+        torch.cuda.synchronize()
+        self.mlp_before = (f64(self.st.mlp_params), [(W.copy(), b.copy()) for W, b in self.orc.mlp])
+        self.flip_total = 0
+
+    def _snapshot(self, batch):
+        for name, table, store, ids in (("user", self.st.user_emb, self.orc.user_emb, batch.user_id),
+                                        ("url", self.st.url_emb, self.orc.url_emb, batch.url_id)):
+            seen = self.before[name]
+            new = np.array(sorted(set(ids.tolist()) - seen.keys()), dtype=np.int64)
+            if len(new):
+                got = f64(table[torch.from_numpy(new).cuda()])
+                ref = store.rows(new)
+                for k, a, b in zip(new.tolist(), got, ref):
+                    seen[k] = (a.copy(), b.copy())
+
+    def step(self, batch: PageViewBatch, lr: float, what: str, flip_cap=None):
+        """Run one step on both sides and compare every output; returns the oracle's result."""
+        wl, st, rel = self.wl, self.st, self.rel
+        self._snapshot(batch)
+        dev = g.DeviceBatch.from_host(batch)
+        if self.adam is None:
+            g.gear_step(st, dev, wl.M, lr)
+        else:
+            g.gear_step_adam(st, dev, wl.M, lr, self.adam)
+        torch.cuda.synchronize()
+        B, d = batch.B, wl.emb_dim
+        assert int(st.status.item()) == 0, what
+        choice = [(st.region(f"h{l}", B) > 0).cpu().numpy() for l in range(len(wl.layers) - 1)]
+        lr32 = float(np.float32(lr))
+        ref = self.orc.step(batch, lr32, relu_choice=choice, kink_tol=self.kink_tol)
+        self.steps += 1
+        for key, t in ref.emb_term_scale.items():
+            self.term[key] = max(self.term.get(key, 0.0), lr32 * t)
+        assert ref.refused_units == 0, \
+            f"{what}: {ref.refused_units} hidden units took another branch than the oracle away from the kink"
+
+        # grouping of the image ids
+        nu = int(st.dbg[3].item())
+        assert nu == len(ref.img_unique), what
+        assert np.array_equal(st.dbg[0][:nu].cpu().numpy(), ref.img_unique), what
+        assert np.array_equal(st.dbg[1][:nu + 1].cpu().numpy(), ref.img_segoff), what
+        assert np.array_equal(st.dbg[2][:batch.nnz].cpu().numpy(), ref.img_perm), what
+
+        # forward
+        wx = assert_rows_close(f64(st.region("x", B)), ref.x, rel, f"{what}: x")
+        wz = assert_rows_close(f64(st.region("logits", B)), ref.logits, rel, f"{what}: logits")
+        assert abs(float(st.loss.item()) - ref.loss) <= rel * abs(ref.loss), (what, st.loss.item(), ref.loss)
+
+        # (1) dLoss/dx against the oracle's own decisions
+        dx = f64(st.region("dx", B))
+        err, scale = row_errors(dx, ref.dx_own)
+        off = err > rel * scale
+        near = ref.near_units > 0
+        assert not (off & ~near).any(), \
+            f"{what}: dx rows off with no unit near a kink: {np.flatnonzero(off & ~near)[:5]}"
+        bound = KINK_C * ref.chosen_per_view / np.sqrt(np.maximum(ref.active_units, 1))
+        assert (err[off] <= bound[off] * scale[off]).all(), \
+            f"{what}: a dx row is off by more than {KINK_C} * (units on the other branch) / sqrt(active units)"
+        worst_flip = float((err[off] / np.maximum(bound[off] * scale[off], 1e-300)).max()) if off.any() else 0.0
+        cap = max(2, 0.002 * B) if wl.mlp_dtype == "f32" else max(2, 0.06 * B)
+        if flip_cap is not None:
+            cap = max(2, flip_cap * B)
+        assert off.sum() <= cap, f"{what}: {off.sum()} of {B} dx rows differ at kinks ({near.sum()} rows are near one)"
+        assert np.median(err / scale) <= rel / 4, f"{what}: median dx row error {np.median(err / scale):.2e}"
+        self.flip_total += int(off.sum())
+
+        # (2) the same branches on both sides: everything by the row rule, nothing exempt
+        wdx = assert_rows_close(dx, ref.dx, rel, f"{what}: dx (same branches)")
+        n_ready = int(st.n_ready.item())
+        assert n_ready == len(ref.ready_ids), what
+        assert np.array_equal(st.ready_ids[:n_ready].cpu().numpy(), ref.ready_ids), what
+        wr = 0.0
+        if n_ready:
+            wr = assert_rows_close(f64(st.ready_grads[:n_ready]), ref.ready_grads, rel, f"{what}: ready_grads",
+                                   term_scale=ref.ready_term_scale)
+        note(f"{what}: B {B}, rows near a kink {int(near.sum())}, rows differing under own decisions {int(off.sum())} "
+             f"(cap {int(cap)}; worst {worst_flip:.2f} of its bound), units given the kernel's branch {ref.chosen_units}; worst error / bar: x {wx / rel:.3f}, "
+             f"logits {wz / rel:.3f}, dx {wdx / rel:.3f}, ready_grads ({n_ready} rows) {wr / rel:.3f}")
+        return ref
+
+    def check_state(self, what, changes=True, resolution=None):
+        """The persistent state: counters bit for bit, accumulators by rows, and what the steps changed
+        in the tables and the MLP as a change (after - before on both sides).  resolution: the median
+        row's change must be at least this many times what the comparison allows it to be off by (above
+        1, a step that left the rows as they were puts more than half of them outside the allowance)."""
+        wl, st, orc, rel = self.wl, self.st, self.orc, self.rel
+        counts = st.counts.cpu().numpy()
+        touched = np.array(sorted(orc.counts), dtype=np.int64)
+        assert int(counts.sum()) == sum(orc.counts.values()), what
+        assert np.array_equal(counts[touched], np.array([orc.counts[i] for i in touched], dtype=np.int32)), what
+        wa = 0.0
+        if len(touched):
+            acc = f64(st.grad_accum[torch.from_numpy(touched).cuda()])
+            ref = np.stack([orc.residual(i) for i in touched])
+            # images whose count is a multiple of M hold exactly zero
+            full = np.array([orc.counts[i] % wl.M == 0 for i in touched])
+            assert not acc[full].any(), what
+            wa = assert_rows_close(acc, ref, rel, f"{what}: grad_accum",
+                                   term_scale=[orc.residual_term_scale(i) for i in touched])
+        # untouched accumulators are still zero
+        nz_rows = int((st.grad_accum != 0).any(dim=1).sum().item())
+        assert nz_rows <= len(touched), what
+        line = f"{what}: {len(touched)} accumulator rows, worst error / bar {wa / rel:.3f}"
+        if not changes:
+            note(line)
+            return
+        for name, table, store in (("user", st.user_emb, orc.user_emb), ("url", st.url_emb, orc.url_emb)):
+            seen = self.before[name]
+            ids = np.array(sorted(seen), dtype=np.int64)
+            if len(ids):
+                got = f64(table[torch.from_numpy(ids).cuda()])
+                worst, res = assert_delta_rows_close(
+                    got, np.stack([seen[k][0] for k in ids.tolist()]), store.rows(ids),
+                    np.stack([seen[k][1] for k in ids.tolist()]), rel, wl.emb_dtype, self.steps, f"{what}: {name}_emb",
+                    term_scale=[self.term[(name, k)] for k in ids.tolist()])
+                line += f"; {name}_emb {len(ids)} rows: worst error / allowance {worst:.3f}, median change / allowance {res:.1f}"
+                if resolution is not None and wl.emb_dtype == "f32":
+                    assert res >= resolution, f"{what}: {name}_emb changes are not resolved ({res:.2f})"
+        gpu_before, ref_before = self.mlp_before
+        for l, (W, b) in enumerate(orc.mlp):
+            Wg, bg = st.layer_params(l)
+            wo, bo = g.gear_mlp_param_offset(self.cfg, l, 0), g.gear_mlp_param_offset(self.cfg, l, 1)
+            worst, res = assert_delta_rows_close(f64(Wg), gpu_before[wo:wo + W.size].reshape(W.shape), W,
+                                                 ref_before[l][0], rel, "f32", self.steps, f"{what}: W{l}")
+            wb, _ = assert_delta_rows_close(f64(bg), gpu_before[bo:bo + b.size], b, ref_before[l][1], rel, "f32",
+                                            self.steps, f"{what}: b{l}")
+            line += f"; W{l} {worst:.3f} (change / allowance {res:.1f}), b{l} {wb:.3f}"
+            if resolution is not None:
+                assert res >= resolution, f"{what}: W{l} changes are not resolved ({res:.2f})"
+        note(line)
 
 
 # ------------------------------------------------------------------ initialiser
@@ -187,15 +276,14 @@ def test_group_ids_matches_brute_force(n, key_range):
 # ------------------------------------------------------------------ full steps
 def test_tiny_all_steps_free_running():
     wl = get_workload("tiny")
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     src = PageViewSource(wl)
     emitted = 0
     for step in range(wl.steps):
-        ref, fv, fi = check_step(wl, st, orc, src.batch(step), wl.lr, f"tiny step {step}")
-        assert len(fv) == 0
+        ref = pair.step(src.batch(step), wl.lr, f"tiny step {step}")
         emitted += len(ref.ready_ids)
-        check_state(wl, st, orc, f"tiny after step {step}")
-    assert emitted > 0
+        pair.check_state(f"tiny after step {step}")
+    assert emitted > 0 and pair.flip_total == 0
 
 
 @pytest.mark.parametrize("name,batch,steps,lr", [
@@ -212,15 +300,12 @@ def test_workload_steps_free_running(name, batch, steps, lr):
         wl = wl.scaled(n_users=200_000, n_urls=1 << 18, n_images=20_000)
     if name == "hotkey":
         wl = wl.scaled(n_images=300)                     # many images pass M = 64 more than once per step
-    cfg, st, orc = make_pair(wl, max_batch=batch)
+    pair = Pair(wl, max_batch=batch)
     src = PageViewSource(wl)
-    fu, fl, fi = set(), set(), set()
     for step in range(steps):
-        b = src.batch(step, batch=batch)
-        ref, fv, imgs = check_step(wl, st, orc, b, lr, f"{name} B={batch} step {step}", earlier_flipped_imgs=fi)
-        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
-        check_state(wl, st, orc, f"{name} B={batch} after step {step}", fu, fl, fi)
-    assert sum(orc.counts.values()) > 0
+        pair.step(src.batch(step, batch=batch), lr, f"{name} B={batch} step {step}")
+        pair.check_state(f"{name} B={batch} after step {step}")
+    assert sum(pair.orc.counts.values()) > 0
 
 
 @pytest.mark.parametrize("dtype,hidden", [
@@ -232,12 +317,11 @@ def test_workload_steps_free_running(name, batch, steps, lr):
 def test_wide_and_narrow_last_hidden_layer(dtype, hidden):
     """The logit/loss kernel picks lanes per view and pieces per lane from the last hidden width."""
     wl = get_workload("tiny").scaled(layers=(*hidden, 1), mlp_dtype=dtype, emb_dtype=dtype, dfv_dtype=dtype)
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     src = PageViewSource(wl)
     for step in range(2):
-        b = src.batch(step, batch=389)
-        check_step(wl, st, orc, b, 0.05, f"{dtype} hidden {hidden} step {step}")
-    check_state(wl, st, orc, f"{dtype} hidden {hidden}")
+        pair.step(src.batch(step, batch=389), 0.05, f"{dtype} hidden {hidden} step {step}")
+    pair.check_state(f"{dtype} hidden {hidden}")
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
@@ -261,48 +345,42 @@ def test_three_hidden_layers(batch):
     k-tile, one launch per layer."""
     wl = get_workload("tiny").scaled(layers=(320, 72, 64, 1), mlp_dtype="bf16", emb_dtype="bf16", dfv_dtype="bf16",
                                      batch=1056)
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     src = PageViewSource(wl)
-    fu, fl, fi = set(), set(), set()
     for step in range(2):
-        b = src.batch(step, batch=batch)
-        ref, fv, imgs = check_step(wl, st, orc, b, 0.5, f"three hidden layers B={batch} step {step}",
-                                   earlier_flipped_imgs=fi)
-        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
-    check_state(wl, st, orc, f"three hidden layers B={batch}", fu, fl, fi)
+        pair.step(src.batch(step, batch=batch), 0.5, f"three hidden layers B={batch} step {step}")
+    pair.check_state(f"three hidden layers B={batch}")
 
 
 def test_batches_smaller_than_the_largest_take_whichever_weight_gradient_path_fits():
     """A state sized for 1500 views (no multiple of 32 rows) steps through batches of 1472 (all weight
     gradients in one launch, more split-K partials than a layer-by-layer step of 1500 needs), 1500 and 700."""
     wl = get_workload("bf16").scaled(n_users=50_000, n_urls=1 << 15, n_images=5_000, M=4)
-    cfg, st, orc = make_pair(wl, max_batch=1500)
+    pair = Pair(wl, max_batch=1500)
     src = PageViewSource(wl)
-    fu, fl, fi = set(), set(), set()
     for step, batch in enumerate((1472, 1500, 700)):
-        b = src.batch(step, batch=batch)
-        ref, fv, imgs = check_step(wl, st, orc, b, 0.05, f"max 1500, B={batch}", earlier_flipped_imgs=fi)
-        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
-    check_state(wl, st, orc, "max 1500", fu, fl, fi)
+        pair.step(src.batch(step, batch=batch), 0.05, f"max 1500, B={batch}")
+    pair.check_state("max 1500")
 
 
 def test_epoch_pattern_free_running():
     """One image per view, every image once per epoch: cold rows each step, groups close after M epochs."""
     wl = get_workload("epoch").scaled(batch=600, n_images=1800, M=2)
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     src = PageViewSource(wl)
     emitted = []
     for step in range(8):                                   # 2 2/3 epochs of three steps
-        ref, _, _ = check_step(wl, st, orc, src.batch(step), wl.lr, f"epoch step {step}")
+        ref = pair.step(src.batch(step), wl.lr, f"epoch step {step}")
         emitted.append(len(ref.ready_ids))
-    check_state(wl, st, orc, "epoch after 8 steps")
+    pair.check_state("epoch after 8 steps")
     assert emitted == [0, 0, 0, 600, 600, 600, 0, 0]
 
 
 def test_expired_ids_and_stamps_match_oracle():
     """Expiry of cached inference results: bit-exact lists over several steps of refresh + stamp."""
     wl = get_workload("hotkey").scaled(n_images=3000, batch=700)
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
+    cfg, st, orc = pair.cfg, pair.st, pair.orc
     stamp = torch.zeros(wl.n_images, dtype=torch.int32, device="cuda")
     src = PageViewSource(wl)
     total = 0
@@ -328,7 +406,7 @@ def test_expired_ids_and_stamps_match_oracle():
     host = stamp.cpu().numpy()
     assert all(host[i] == t for i, t in orc.stamps.items()) and int((host != 0).sum()) <= len(orc.stamps)
     # refreshed rows are what the next step gathers
-    check_step(wl, st, orc, src.batch(20), wl.lr, "step after refreshes")
+    pair.step(src.batch(20), wl.lr, "step after refreshes")
     # empty request, and an id out of range
     out, n_out = g.gear_expired_ids(st, torch.zeros(0, dtype=torch.int32, device="cuda"), stamp, 50, 0)
     torch.cuda.synchronize()
@@ -417,62 +495,54 @@ def test_adam_steps_free_running(name, batch, eps):
     lr, steps = 1e-3, 3
     if name != "tiny":
         wl = wl.scaled(n_users=50_000, n_urls=1 << 15, n_images=20_000)
-    cfg, st, orc = make_pair(wl, max_batch=batch)
-    orc.use_adam(eps=eps)
-    adam = g.AdamMoments(st, eps=eps)
+    pair = Pair(wl, max_batch=batch, adam_eps=eps)
+    cfg, st, orc, adam = pair.cfg, pair.st, pair.orc, pair.adam
     src = PageViewSource(wl)
     rel = REL[wl.mlp_dtype]
     strict = eps >= 1e-4
-    fu, fl, fi = set(), set(), set()
     for step in range(steps):
-        b = src.batch(step, batch=batch)
         # Adam moves every weight by about the rate each step; where the two sides' updates differ in the
         # last bits a bf16 operand copy can round the other way (a few hundred of 3e5 weights), which
-        # shifts every view's pre-activations a little: more units flip than under SGD
-        ref, fv, imgs = check_step(wl, st, orc, b, lr, f"adam {name} step {step}", adam=adam,
-                                   flip_cap=0.15 if wl.mlp_dtype == "bf16" else None)
-        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
+        # shifts every view's pre-activations a little: more units land on the other side of the kink than under SGD
+        pair.step(src.batch(step, batch=batch), lr, f"adam {name} eps {eps:g} step {step}",
+                  flip_cap=0.15 if wl.mlp_dtype == "bf16" else None)
     assert adam.t == steps == orc.adam.t
     torch.cuda.synchronize()
+    pair.check_state(f"adam {name} eps {eps:g}", changes=False)
 
-    def moments_close(got, want, tol, what, exempt=None):
-        # a moment row is a gradient row: in bf16 a unit that takes the other ReLU branch for one view
-        # moves its whole row by about 1/sqrt(views), so there most rows must pass and none may be far off
-        if wl.mlp_dtype != "bf16":
-            return assert_rows_close(got, want, tol, what, exempt=exempt)
-        err, scale = row_errors(got, want)
-        off = err > tol * scale
-        if exempt is not None:
-            off &= ~exempt
-        assert off.mean() <= 0.10 and (err[off] <= 0.3 * scale[off]).all(), (what, int(off.sum()), len(off))
-
-    def params_close(got, want, what, exempt=None):
+    # Both sides took the same ReLU branches (Pair), so a moment row is held to the row rule like any
+    # other row.  The second moment is quadratic in the gradient: twice the relative bar.
+    def params_close(got, want, what):
         if strict:
-            assert_rows_close(got, want, rel, what, exempt=exempt)
+            assert_rows_close(got, want, rel, what)
         else:
             bad = np.abs(got - want).reshape(len(want), -1).max(axis=1) > rel * np.abs(want).max() + 2 * steps * lr
-            assert not (bad & ~(np.zeros(len(bad), bool) if exempt is None else exempt)).any(), what
+            assert not bad.any(), what
 
+    worst = {}
     for l, (W, bvec) in enumerate(orc.mlp):
         Wg, bg = st.layer_params(l)
         params_close(f64(Wg), W, f"adam W{l}")
         params_close(f64(bg).reshape(1, -1), bvec.reshape(1, -1), f"adam b{l}")
         wo, n = g.gear_mlp_param_offset(cfg, l, 0), W.size
         m_ref, v_ref = orc.adam.moments[("W", l)]
-        moments_close(f64(adam.mlp_m[wo:wo + n]).reshape(W.shape), m_ref, rel, f"adam m W{l}")
-        moments_close(f64(adam.mlp_v[wo:wo + n]).reshape(W.shape), v_ref, 2 * rel, f"adam v W{l}")
-    for tag, table, store, mt, vt, flipped in (("user", st.user_emb, orc.user_emb, adam.user_m, adam.user_v, fu),
-                                               ("url", st.url_emb, orc.url_emb, adam.url_m, adam.url_v, fl)):
+        worst[f"m W{l}"] = assert_rows_close(f64(adam.mlp_m[wo:wo + n]).reshape(W.shape), m_ref, rel, f"adam m W{l}") / rel
+        worst[f"v W{l}"] = assert_rows_close(f64(adam.mlp_v[wo:wo + n]).reshape(W.shape), v_ref, 2 * rel, f"adam v W{l}") / (2 * rel)
+    for tag, table, store, mt, vt in (("user", st.user_emb, orc.user_emb, adam.user_m, adam.user_v),
+                                      ("url", st.url_emb, orc.url_emb, adam.url_m, adam.url_v)):
         ids = np.array(sorted(k for (t, k) in orc.adam.moments if t == tag), dtype=np.int64)
         assert len(ids)
         idx = torch.from_numpy(ids).cuda()
-        ex = np.isin(ids, list(flipped))
         m_ref = np.stack([orc.adam.moments[(tag, int(k))][0] for k in ids])
         v_ref = np.stack([orc.adam.moments[(tag, int(k))][1] for k in ids])
-        moments_close(f64(mt[idx]), m_ref, rel, f"adam m {tag}", exempt=ex)
-        moments_close(f64(vt[idx]), v_ref, 2 * rel, f"adam v {tag}", exempt=ex)
+        # a moment row of a table is a sum of per-view gradient terms: measured against the largest of them
+        term = np.array([pair.term[(tag, int(k))] / lr for k in ids])
+        worst[f"m {tag}"] = assert_rows_close(f64(mt[idx]), m_ref, rel, f"adam m {tag}", term_scale=(1 - adam.beta1) * term) / rel
+        worst[f"v {tag}"] = assert_rows_close(f64(vt[idx]), v_ref, 2 * rel, f"adam v {tag}",
+                                              term_scale=(1 - adam.beta2) * term ** 2) / (2 * rel)
         assert int((mt != 0).any(dim=1).sum().item()) <= len(ids)          # only touched rows moved
-        params_close(f64(table[idx]), np.stack([store.row(int(k)) for k in ids]), f"adam {tag} rows", exempt=ex)
+        params_close(f64(table[idx]), np.stack([store.row(int(k)) for k in ids]), f"adam {tag} rows")
+    note(f"adam {name} eps {eps:g}: worst moment error / bar " + ", ".join(f"{k} {v:.3f}" for k, v in worst.items()))
 
 
 @pytest.mark.parametrize("name,device_count", [("small", False), ("bf16", False), ("small", True), ("bf16", True)])
@@ -482,7 +552,8 @@ def test_dense_standin_closes_the_loop(name, device_count):
     from oracle.dense_standin import DenseStandIn as OracleDense
     wl = get_workload(name).scaled(n_users=50_000, n_urls=1 << 15, n_images=3_000, M=4)
     batch, r = 900, 16
-    cfg, st, orc = make_pair(wl, max_batch=batch)
+    pair = Pair(wl, max_batch=batch)
+    cfg, st, orc = pair.cfg, pair.st, pair.orc
     gen = torch.Generator(device="cpu").manual_seed(5)
     raw = torch.randn(wl.n_images, r, generator=gen)
     wd = torch.randn(wl.dfv_dim, r, generator=gen) / r ** 0.5
@@ -491,7 +562,7 @@ def test_dense_standin_closes_the_loop(name, device_count):
     rel = REL[wl.mlp_dtype]
     src = PageViewSource(wl)
     all_ids = np.arange(wl.n_images)
-    emitted, fi = 0, set()
+    emitted = 0
     for step in range(3):
         # Slowgear inference for the whole image set (here: every step), written into both caches
         rows = dense.infer(None, wl.n_images)
@@ -502,8 +573,7 @@ def test_dense_standin_closes_the_loop(name, device_count):
         g.gear_refresh_dfv(st, None, rows)
         orc.refresh_dfv(all_ids, ref_rows)          # from the oracle's own stand-in: nothing crosses over
         b = src.batch(step, batch=batch)
-        ref, fv, imgs = check_step(wl, st, orc, b, wl.lr, f"{name} closed loop step {step}", earlier_flipped_imgs=fi)
-        fi.update(imgs)
+        ref = pair.step(b, wl.lr, f"{name} closed loop step {step}")
         n = int(st.n_ready.item())
         emitted += n
         if device_count:
@@ -534,16 +604,70 @@ def test_large_workload_at_full_size():
     DFVs, B = 65 536, the launch shapes bench.py times.  The oracle materialises only the rows the two
     steps touch; every output and every touched row of the 46 GB of state is compared."""
     wl = get_workload("large")
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     src = PageViewSource(wl)
-    fu, fl, fi = set(), set(), set()
     for step in range(2):
         b = src.batch(step)
         assert b.B == 65536
-        ref, fv, imgs = check_step(wl, st, orc, b, wl.lr, f"large full size step {step}", earlier_flipped_imgs=fi)
-        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
-    check_state(wl, st, orc, "large full size", fu, fl, fi)
-    assert int(st.n_ready.item()) > 10_000
+        pair.step(b, wl.lr, f"large full size step {step}")
+    # at the workload's own rate the changes of the table rows and of the weights are a few units in the
+    # last place of the stored values; compared as changes they are resolved (a step that left the
+    # tables or the weights alone would fail here)
+    pair.check_state("large full size", resolution=1.5)
+    assert int(pair.st.n_ready.item()) > 10_000
+
+
+@pytest.mark.parametrize("name", ["bf16", "hotkey"])
+def test_workload_at_full_size(name):
+    """The bf16 and the hot-key workloads exactly as configured (B = 16 384; 10 M users, 2^24 URL buckets,
+    1 M images of 512 bf16, M = 32; and 1 M users, 2^22 buckets, 10 000 images under Zipf 1.5 with up to
+    16 per view, M = 64, where the most popular image closes hundreds of groups in one step): two
+    free-running steps, every output and every touched row."""
+    wl = get_workload(name)
+    pair = Pair(wl)
+    src = PageViewSource(wl)
+    emitted = 0
+    for step in range(2):
+        b = src.batch(step)
+        assert b.B == 16384
+        ref = pair.step(b, wl.lr, f"{name} full size step {step}")
+        emitted += len(ref.ready_ids)
+    pair.check_state(f"{name} full size", resolution=1.5)
+    if name == "hotkey":
+        top = np.bincount(src.batch(1).img_id).max()
+        assert top > 20_000 and emitted > 3000          # one image alone closes several hundred groups of 64
+
+
+def test_small_workload_twenty_steps_free_running_then_integers_to_one_hundred():
+    """The small workload as configured: twenty steps with every float compared, both sides running
+    freely from their own initial state, then on to its hundred steps with counts and ready lists
+    held to their definition (Section 1, third point)."""
+    wl = get_workload("small")
+    pair = Pair(wl)
+    src = PageViewSource(wl)
+    for step in range(20):
+        pair.step(src.batch(step), wl.lr, f"small step {step}")
+        if step in (0, 9, 19):
+            pair.check_state(f"small after step {step}")
+    st = pair.st
+    counts = np.zeros(wl.n_images, dtype=np.int64)
+    for i, c in pair.orc.counts.items():
+        counts[i] = c
+    for step in range(20, wl.steps):
+        b = src.batch(step)
+        g.gear_step(st, g.DeviceBatch.from_host(b), wl.M, wl.lr)
+        n_i = np.bincount(b.img_id, minlength=wl.n_images)
+        emits = (counts + n_i) // wl.M - counts // wl.M
+        counts += n_i
+        expect = np.repeat(np.arange(wl.n_images, dtype=np.int32), emits)
+        torch.cuda.synchronize()
+        n = int(st.n_ready.item())
+        assert int(st.status.item()) == 0 and n == len(expect), (step, n, len(expect))
+        assert np.array_equal(st.ready_ids[:n].cpu().numpy(), expect), step
+        assert np.isfinite(float(st.loss.item())) and torch.isfinite(st.ready_grads[:n]).all()
+    assert np.array_equal(st.counts.cpu().numpy(), counts.astype(np.int32))
+    acc_nz = (st.grad_accum != 0).any(dim=1).cpu().numpy()
+    assert not acc_nz[counts % wl.M == 0].any()
 
 
 def test_integer_outputs_over_many_steps():
@@ -583,14 +707,11 @@ def test_integer_outputs_over_many_steps():
 def test_every_combination_of_storage_types(emb, dfv, mlp):
     """Tables, cache and MLP operands each in fp32 or bf16: all eight gather / update variants."""
     wl = get_workload("tiny").scaled(emb_dtype=emb, dfv_dtype=dfv, mlp_dtype=mlp, layers=(64, 32, 1), M=3)
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     src = PageViewSource(wl)
-    fu, fl, fi = set(), set(), set()
     for step in range(2):
-        b = src.batch(step, batch=300)
-        ref, fv, imgs = check_step(wl, st, orc, b, 0.5, f"{emb}/{dfv}/{mlp} step {step}", earlier_flipped_imgs=fi)
-        fu.update(b.user_id[fv].tolist()); fl.update(b.url_id[fv].tolist()); fi.update(imgs)
-    check_state(wl, st, orc, f"{emb}/{dfv}/{mlp}", fu, fl, fi)
+        pair.step(src.batch(step, batch=300), 0.5, f"{emb}/{dfv}/{mlp} step {step}")
+    pair.check_state(f"{emb}/{dfv}/{mlp}")
 
 
 def test_same_step_twice_is_bit_identical():
@@ -638,18 +759,18 @@ def test_one_stream_and_two_streams_give_the_same_bits(name, batch):
 # ------------------------------------------------------------------ edge cases
 def test_empty_views_duplicates_and_single_view():
     wl = get_workload("tiny").scaled(M=2)
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
     b = batch_from_lists([1, 1, 7, 999], [0, 4095, 5, 5], [[], [3, 3, 3], [1999], []], [1, 0, 0, 1])
-    ref, _, _ = check_step(wl, st, orc, b, 0.5, "empty views")
+    ref = pair.step(b, 0.5, "empty views")
     assert ref.ready_ids.tolist() == [3]
-    check_state(wl, st, orc, "empty views")
+    pair.check_state("empty views")
     b1 = batch_from_lists([0], [0], [[3, 0, 3]], [0])
-    ref, _, _ = check_step(wl, st, orc, b1, 0.5, "single view")
+    ref = pair.step(b1, 0.5, "single view")
     assert ref.ready_ids.tolist() == [3]             # one kept gradient + two new ones: one group of M = 2
-    check_state(wl, st, orc, "single view")
+    pair.check_state("single view")
     b2 = batch_from_lists([5, 6], [1, 2], [[], []], [0, 1])     # no image at all
-    check_step(wl, st, orc, b2, 0.5, "no occurrences")
-    check_state(wl, st, orc, "no occurrences")
+    pair.step(b2, 0.5, "no occurrences")
+    pair.check_state("no occurrences")
 
 
 def test_batch_of_zero_views_is_a_no_op():
@@ -668,14 +789,15 @@ def test_batch_of_zero_views_is_a_no_op():
 
 def test_maximum_batch_and_nnz():
     wl = get_workload("tiny")
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
+    cfg = pair.cfg
     rng = np.random.default_rng(9)
     views = [rng.integers(0, wl.n_images, wl.max_images).tolist() for _ in range(wl.batch)]   # nnz = max_nnz
     b = batch_from_lists(rng.integers(0, wl.n_users, wl.batch), rng.integers(0, wl.n_urls, wl.batch), views,
                          rng.integers(0, 2, wl.batch))
     assert b.nnz == cfg.max_nnz
-    check_step(wl, st, orc, b, 0.1, "max sizes")
-    check_state(wl, st, orc, "max sizes")
+    pair.step(b, 0.1, "max sizes")
+    pair.check_state("max sizes")
 
 
 def _error_path_workload(one_launch):
@@ -720,8 +842,42 @@ def test_ready_list_over_capacity_is_reported_and_changes_nothing(one_launch):
     g.gear_step(st, g.DeviceBatch.from_host(PageViewSource(wl).batch(0)), wl.M, wl.lr)   # nnz > 100 emissions
     torch.cuda.synchronize()
     assert int(st.status.item()) == g.GEAR_ERR_CAPACITY
+    assert int(st.n_ready.item()) == 0               # a list that does not fit reads as empty, not as its length
     for a, b in zip(before, (st.user_emb, st.mlp_params, st.grad_accum, st.counts)):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["tiny", "large"])
+def test_a_step_that_fails_part_way_still_joins_the_helper_stream(name):
+    """A launch that fails in the middle of a step's enqueue (forced from the host: the n-th launch is
+    not enqueued and the call returns GEAR_ERR_HIP) must leave the caller's stream waiting for whatever
+    the call had already put on the helper stream: once the caller's stream has drained, the helper
+    stream has nothing left to run, wherever the step stopped.  A fresh state then steps normally."""
+    wl = get_workload(name)
+    if name == "large":                                # two hidden bf16 layers: dLoss/dx in two products, one wgrad launch
+        wl = wl.scaled(n_users=100_000, n_urls=1 << 16, n_images=5_000, batch=8192)
+    cfg, st, _ = make_pair(wl)
+    dev = g.DeviceBatch.from_host(PageViewSource(wl).batch(0))
+    stream = torch.cuda.current_stream()
+    n_fail = 0
+    try:
+        for nth in range(1, 40):
+            g.gear_debug_fail_launch(nth)
+            try:
+                g.gear_step(st, dev, wl.M, wl.lr)
+            except g.GearError as e:
+                assert e.code == g.GEAR_ERR_HIP
+                n_fail += 1
+                stream.synchronize()                   # the caller's stream only
+                assert g.gear_debug_helper_idle() == 1, f"launch {nth}: helper stream still busy after the caller's drained"
+            else:
+                break                                  # nth is beyond the step's last launch: the step ran whole
+    finally:
+        g.gear_debug_fail_launch(0)
+    torch.cuda.synchronize()
+    assert n_fail >= 10
+    pair = Pair(wl)
+    pair.step(PageViewSource(wl).batch(0), wl.lr, f"{name} after failed enqueues")
 
 
 def test_host_checked_arguments():
@@ -745,9 +901,10 @@ def test_host_checked_arguments():
 # ------------------------------------------------------------------ cache refresh
 def test_refresh_overwrites_rows_and_nothing_else():
     wl = get_workload("tiny")
-    cfg, st, orc = make_pair(wl)
+    pair = Pair(wl)
+    cfg, st, orc = pair.cfg, pair.st, pair.orc
     src = PageViewSource(wl)
-    check_step(wl, st, orc, src.batch(0), wl.lr, "before refresh")
+    pair.step(src.batch(0), wl.lr, "before refresh")
     accum, counts = st.grad_accum.clone(), st.counts.clone()
     ids = np.array([5, 1999, 0, 77], dtype=np.int32)
     rows = np.random.default_rng(3).normal(0, 1, (4, wl.dfv_dim)).astype(np.float32)
@@ -760,8 +917,8 @@ def test_refresh_overwrites_rows_and_nothing_else():
     mask = torch.ones(wl.n_images, dtype=torch.bool, device="cuda")
     mask[torch.from_numpy(ids.astype(np.int64)).cuda()] = False
     assert torch.equal(old[mask], st.dfv_cache[mask])
-    check_step(wl, st, orc, src.batch(1), wl.lr, "after refresh")
-    check_state(wl, st, orc, "after refresh")
+    pair.step(src.batch(1), wl.lr, "after refresh")
+    pair.check_state("after refresh")
     # whole-table refresh (image_ids = NULL) and an out-of-range id
     full = torch.randn((wl.n_images, wl.dfv_dim), device="cuda")
     g.gear_refresh_dfv(st, None, full)

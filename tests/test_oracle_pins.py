@@ -441,6 +441,63 @@ def test_bf16_mode_rounds_operands():
     assert all(np.array_equal(W, round_to(W, "f32")) for W, _ in o.mlp)
 
 
+def test_branch_choice_is_taken_only_within_rounding_distance_of_the_kink():
+    """step(relu_choice=...) follows a given ReLU branch only at units whose pre-activation is within
+    kink_tol of zero; elsewhere the oracle keeps its own decision and counts the refusal.
+
+    One view, two hidden units: a = [2^-20, 1].  Unit 0 is on by the oracle's own arithmetic but within
+    1e-5 of the kink relative to the layer's largest pre-activation; unit 1 is far from it."""
+    def build():
+        W1 = np.array([[2.0 ** -20, 0.0, 0.0], [0.0, 0.0, 1.0]])
+        return GearOracle(RowStore(1, 1, "f64", dense=np.array([[1.0]])), RowStore(1, 1, "f64", dense=np.array([[0.0]])),
+                          RowStore(1, 1, "f64", dense=np.array([[1.0]])),
+                          [(W1, np.zeros(2)), (np.array([[4.0, -1.0]]), np.array([1.0]))], 1, Precision.exact())
+    batch = batch_from_lists([0], [0], [[0]], [1])
+    own = build().step(batch, 0.0)
+    assert own.dx[0, 0] != 0.0 and own.near_units.tolist() == [0] and np.array_equal(own.dx, own.dx_own)
+    on, off = np.array([[True, True]]), np.array([[False, True]])
+    same = build().step(batch, 0.0, relu_choice=[on], kink_tol=1e-5)
+    assert np.array_equal(same.dx, own.dx) and same.chosen_units == 0 and same.refused_units == 0
+    assert same.near_units.tolist() == [1] and same.active_units.tolist() == [2]
+    flipped = build().step(batch, 0.0, relu_choice=[off], kink_tol=1e-5)
+    # unit 0 off: its delta is zero, so dLoss/dx loses that unit's term; the own-decision result is kept beside it
+    assert flipped.chosen_units == 1 and flipped.refused_units == 0
+    assert flipped.dx[0, 0] == 0.0 and np.array_equal(flipped.dx_own, own.dx)
+    assert np.array_equal(flipped.dx[0, 2:], own.dx[0, 2:]) or abs(flipped.logits[0] - own.logits[0]) < 1e-5
+    # the far unit cannot be flipped, whatever the choice says; nor can any unit when kink_tol is 0
+    far = build().step(batch, 0.0, relu_choice=[np.array([[True, False]])], kink_tol=1e-5)
+    assert far.refused_units == 1 and far.chosen_units == 0 and np.array_equal(far.dx, own.dx)
+    none = build().step(batch, 0.0, relu_choice=[off], kink_tol=0.0)
+    assert none.refused_units == 1 and np.array_equal(none.dx, own.dx)
+
+
+def test_branch_choice_decides_what_the_step_applies():
+    """The state after a step follows the chosen branches (weights, rows, stored gradients), so that two
+    arithmetics that agree on the branches stay together over many steps."""
+    rng = np.random.default_rng(8)
+    a, b = small_oracle(rng), small_oracle(np.random.default_rng(8))
+    batch = random_batch(np.random.default_rng(9), 6, 7, 5, 9)
+    ra = a.step(batch, 0.1)
+    # every unit declared ambiguous (kink_tol above 1) and the opposite branch asked for at one active
+    # unit of the first hidden layer; the layers above are given the branches that follow from it
+    choice, x, flipped_unit = [], ra.x, None
+    for l in range(len(a.mlp) - 1):
+        pre = x @ b.mlp[l][0].T + b.mlp[l][1]
+        act = pre > 0
+        if l == 0:
+            flipped_unit = tuple(np.argwhere(act)[0])
+            act[flipped_unit] = False
+        choice.append(act)
+        x = np.where(act, pre, 0.0)
+    v, u = flipped_unit
+    rb = b.step(batch, 0.1, relu_choice=choice, kink_tol=2.0)
+    assert rb.chosen_units == 1 and not np.array_equal(rb.dx[v], ra.dx[v]) and np.array_equal(rb.dx_own, ra.dx)
+    assert not np.array_equal(a.mlp[0][0][u], b.mlp[0][0][u])                # the unit's weight row saw another gradient
+    others = [w for w in range(batch.B) if w != v]
+    assert np.array_equal(rb.dx[others], ra.dx[others])
+    assert not np.array_equal(a.user_emb.row(batch.user_id[v]), b.user_emb.row(batch.user_id[v]))
+
+
 # ------------------------------------------------------------------ workload recipe
 def test_workload_batches_are_reproducible_and_in_range():
     wl = get_workload("tiny")
