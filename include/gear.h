@@ -168,6 +168,22 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *batch, gear_tabl
                       const void *dfv_cache, float *grad_accum, int32_t *counts, int32_t M, float lr,
                       void *workspace, size_t workspace_bytes, gear_step_out *out, void *stream);
 
+/* gear_step for callers that cannot allocate device memory or must not see an allocation happen:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace
+ * is a static device array inside the library (64 MiB = 67 108 864 bytes per GPU, held until the
+ * process ends) instead of a caller's buffer, and every kernel is launched on the caller's stream
+ * (no helper stream, no event).  The call allocates nothing.  Configurations whose
+ * gear_workspace_bytes(cfg) exceeds 67 108 864 are rejected with GEAR_ERR_CAPACITY and nothing is
+ * enqueued (of the workloads this library is measured on that admits batches of about 8 000 views
+ * with 256-wide DFVs; the largest needs 760 MiB and has to bring its own workspace to gear_step).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two host threads) race on it and must be ordered by the caller; nothing in it has to survive
+ * between calls and nothing in it has to be cleared beforehand.  Inputs, outputs, alignment, errors
+ * and results (bit for bit) as for gear_step with one_stream set. */
+gear_status gear_step_static(const gear_config *cfg, const gear_batch *batch, gear_tables *tables,
+                             const void *dfv_cache, float *grad_accum, int32_t *counts, int32_t M, float lr,
+                             gear_step_out *out, void *stream);
+
 /* Adam for the Sparse Part (Section 4.1 trains with the Adam optimiser at rate 1e-4; its other
  * constants are not given).  Kingma & Ba, Algorithm 1, at step t = 1, 2, ...:
  *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgear.so"
 
 EXPORTS = (
     "gear_workspace_bytes", "gear_mlp_param_count", "gear_mlp_param_offset", "gear_workspace_region",
-    "gear_fill_normal", "gear_init_tables", "gear_step", "gear_step_adam", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
+    "gear_fill_normal", "gear_init_tables", "gear_step", "gear_step_static", "gear_step_adam", "gear_refresh_dfv", "gear_expired_ids", "gear_stamp_dfv",
     "gear_refresh_dfv_n", "gear_stamp_dfv_n",
     "gear_dense_workspace_bytes", "gear_dense_infer", "gear_dense_backward", "gear_dense_backward_n", "gear_group_ids",
     "gear_gemm", "gear_profile_create", "gear_profile_destroy", "gear_profile_count", "gear_profile_span",
@@ -91,6 +91,9 @@ def _load() -> C.CDLL:
     lib.gear_step.argtypes = [cfgp, C.POINTER(gear_batch), C.POINTER(gear_tables), C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_size_t,
                               C.POINTER(gear_step_out), C.c_void_p]
+    lib.gear_step_static.restype = C.c_int
+    lib.gear_step_static.argtypes = [cfgp, C.POINTER(gear_batch), C.POINTER(gear_tables), C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_int32, C.c_float, C.POINTER(gear_step_out), C.c_void_p]
     lib.gear_step_adam.restype = C.c_int
     lib.gear_step_adam.argtypes = [cfgp, C.POINTER(gear_batch), C.POINTER(gear_tables), C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_int32, C.c_float, C.POINTER(gear_adam), C.c_void_p, C.c_size_t,
@@ -362,6 +365,14 @@ def gear_step(state: GearState, batch: DeviceBatch, M: int, lr: float) -> None:
     _check(lib.gear_step(C.byref(state.cfg), C.byref(b), C.byref(t), _ptr(state.dfv_cache), _ptr(state.grad_accum),
                          _ptr(state.counts), M, lr, _ptr(state.workspace), state.workspace.numel(), C.byref(o),
                          _stream()), "gear_step")
+
+
+def gear_step_static(state: GearState, batch: DeviceBatch, M: int, lr: float) -> None:
+    """gear_step on the library's static scratch array instead of state.workspace (allocates nothing)."""
+    t, b, o = state.tables(), batch.as_struct(), state.step_out()
+    _check(lib.gear_step_static(C.byref(state.cfg), C.byref(b), C.byref(t), _ptr(state.dfv_cache),
+                                _ptr(state.grad_accum), _ptr(state.counts), M, lr, C.byref(o), _stream()),
+           "gear_step_static")
 
 
 class AdamMoments:

@@ -196,6 +196,32 @@ bool make_layout(const gear_config &c, Layout *lay) {
 
 using namespace gear;
 
+// Scratch memory of gear_step_static: one array per device, inside the code object, so that the call
+// needs no allocation.  In host code the array's name only stands for the symbol; the address of a
+// device's copy comes from hipGetSymbolAddress with that device current, and that address is what
+// the kernels are given.
+#define GEAR_STATIC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[GEAR_STATIC_SCRATCH_BYTES];
+
+namespace {
+void *g_scratch_ptr[64];
+std::mutex g_scratch_mutex;
+
+// address of the current device's copy of `scratch` (looked up once per device); nullptr on failure
+void *static_scratch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    if ((uintptr_t)ptr & 255u) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
 // One helper stream and two events per device, created on first use and kept for the life of the
 // process: the integer grouping of a step runs beside its gather and forward pass.
 namespace {
@@ -363,6 +389,7 @@ gear_status gear_init_tables(const gear_config *cfg, gear_tables *t, float *grad
   if (!make_layout(*cfg, &lay) || !aligned16(grad_accum) || !aligned16(counts) || !aligned16(t->mlp_params))
     return GEAR_ERR_INVALID;
   hipStream_t s = (hipStream_t)stream;
+  if (!static_scratch()) return GEAR_ERR_HIP;  // looked up here so that a later gear_step_static need not
   GEAR_HIP(launch_fill_normal(t->user_emb, cfg->emb_dtype, cfg->n_users * cfg->emb_dim, cfg->seed, 1u,
                               cfg->emb_init_std, s));
   GEAR_HIP(launch_fill_normal(t->url_emb, cfg->emb_dtype, cfg->n_urls * cfg->emb_dim, cfg->seed, 2u,
@@ -380,6 +407,21 @@ gear_status gear_step(const gear_config *cfg, const gear_batch *b, gear_tables *
                       float *grad_accum, int32_t *counts, int32_t M, float lr, void *workspace,
                       size_t workspace_bytes, gear_step_out *out, void *stream) {
   return gear_step_adam(cfg, b, t, dfv_cache, grad_accum, counts, M, lr, nullptr, workspace, workspace_bytes, out,
+                        stream);
+}
+
+gear_status gear_step_static(const gear_config *cfg, const gear_batch *b, gear_tables *t, const void *dfv_cache,
+                             float *grad_accum, int32_t *counts, int32_t M, float lr, gear_step_out *out,
+                             void *stream) {
+  Layout lay;
+  if (!cfg || !out || !make_layout(*cfg, &lay)) return GEAR_ERR_INVALID;
+  if (lay.total > GEAR_STATIC_SCRATCH_BYTES) return GEAR_ERR_CAPACITY;
+  void *ws = static_scratch();
+  if (!ws) return GEAR_ERR_HIP;
+  // every kernel on the caller's stream: no helper stream or event has to exist
+  gear_step_out o = *out;
+  o.one_stream = 1;
+  return gear_step_adam(cfg, b, t, dfv_cache, grad_accum, counts, M, lr, nullptr, ws, GEAR_STATIC_SCRATCH_BYTES, &o,
                         stream);
 }
 
