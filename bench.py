@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--cpu-sample-views", type=int, default=131072,
+    ap.add_argument("--cpu-sample-views", type=int, default=65536,
                     help="views of the oracle's timed sample (0 = skip the CPU baseline)")
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
                     help="sgd is the workload's; adam (beta 0.9 / 0.999, eps 1e-8) is the paper's experiments' choice")
@@ -53,6 +53,9 @@ def parse_args():
                     help="also run the timed steps with every kernel on one stream, one after another (the per-kernel "
                          "pass always does): the whole command then launches each kernel alone, which is what a "
                          "kernel-trace profile should see when its averages are compared with `kernels`")
+    ap.add_argument("--record-mfma", metavar="CSV",
+                    help="no GPU work: write profiles/gear_step_large_mfma_busy.txt from the counter CSV of a rocprofv3 --pmc "
+                         "SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE run of this benchmark")
     ap.add_argument("--record-traffic", nargs="+", metavar="CSV",
                     help="no GPU work: FETCH_CSV WRITE_CSV [BENCH_LOG]: write profiles/traffic.json and the summary "
                          "profiles/gear_step_large_hbm_traffic.txt from two rocprofv3 --pmc counter CSVs of this benchmark "
@@ -101,18 +104,22 @@ class WorkModel:
 
 CSRC = os.path.join(ROOT, "paper_1806_03925_amd", "csrc")
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
-# span -> (substring of the kernel's name, launches of that kernel in one step, index among them in
-# launch order, source files whose change invalidates the recorded figure)
+# span -> (parts, source files whose change invalidates the recorded figure); a part is (substring of
+# the kernel's name, launches of that kernel in one step, index among them in launch order), and a
+# span made of several launches is the sum of its parts
 TRAFFIC_KERNELS = {
-    "gather_pool": ("k_gather_pool", 1, 0, ["gather.hip"]),
-    "accumulate": ("k_accumulate", 1, 0, ["accum.hip"]),
-    "fwd_gemm_l0": ("k_gemm_nt_dma<0>", 2, 0, ["gemm.hip"]),
-    "fwd_gemm_l1": ("k_gemm_nt_dma<0>", 2, 1, ["gemm.hip"]),
-    "dgrad_gemm_l1": ("k_gemm_nt_dma<4>", 1, 0, ["gemm.hip"]),   # masked by the sign bitmap
-    "dgrad_gemm_emb": ("k_gemm_nt_dma<3>", 2, 0, ["gemm.hip"]),
-    "dgrad_gemm_l0": ("k_gemm_nt_dma<3>", 2, 1, ["gemm.hip"]),
-    "wgrad_gemm": ("k_gemm_tn_dma_batch", 1, 0, ["gemm.hip"]),
+    "gather_pool": ([("k_gather_pool", 1, 0)], ["gather.hip"]),
+    "accumulate": ([("k_accumulate", 1, 0)], ["accum.hip"]),
+    "embedding_update": ([("k_embedding_chunks", 1, 0), ("k_embedding_spans", 1, 0)], ["update.hip"]),
+    "fwd_gemm_l0": ([("k_gemm_nt_dma<0>", 2, 0)], ["gemm.hip"]),
+    "fwd_gemm_l1": ([("k_gemm_nt_dma<0>", 2, 1)], ["gemm.hip"]),
+    "dgrad_gemm_l1": ([("k_gemm_nt_dma<4>", 1, 0)], ["gemm.hip"]),   # masked by the sign bitmap
+    "dgrad_gemm_emb": ([("k_gemm_nt_dma<3>", 2, 0)], ["gemm.hip"]),
+    "dgrad_gemm_l0": ([("k_gemm_nt_dma<3>", 2, 1)], ["gemm.hip"]),
+    "wgrad_gemm": ([("k_gemm_tn_dma_batch", 1, 0)], ["gemm.hip"]),
 }
+# launches whose matrix-pipe occupancy is reported (same part notation)
+MFMA_KERNELS = {k: v[0] for k, v in TRAFFIC_KERNELS.items() if "gemm" in k}
 
 
 def source_hash(files):
@@ -127,7 +134,7 @@ def recorded_traffic(span):
     if not os.path.exists(TRAFFIC_FILE) or span not in TRAFFIC_KERNELS:
         return None
     rec = json.load(open(TRAFFIC_FILE)).get("kernels", {}).get(span)
-    if rec is None or rec.get("source_hash") != source_hash(TRAFFIC_KERNELS[span][3]):
+    if rec is None or rec.get("source_hash") != source_hash(TRAFFIC_KERNELS[span][1]):
         return None
     return rec["bytes"]
 
@@ -161,7 +168,8 @@ def write_traffic_summary(rec, refresh_bytes, bench_log=None):
         line = [l for l in open(bench_log) if l.startswith("{")][-1]
         alg = {r["name"]: r.get("algorithmic_per_launch") for r in json.loads(line)["kernels"]}
         lines.append("# algorithmic bytes per launch in the same steps (this benchmark's work model): "
-                     f"accumulate {alg['accumulate'] / 1e6:.1f} MB, gather_pool {alg['gather_pool'] / 1e6:.1f} MB")
+                     f"accumulate {alg['accumulate'] / 1e6:.1f} MB, gather_pool {alg['gather_pool'] / 1e6:.1f} MB, "
+                     f"embedding_update {alg['embedding_update'] / 1e6:.1f} MB")
         lines.append("# (accumulate's grows with the step number, as more images carry a partial sum that has to be read: "
                      "about 850 MB around step 100)")
     lines += ["# the excess is re-reads of dLoss/dx rows (accumulate: one row per occurrence, 4.5 per view) and of cached "
@@ -196,14 +204,16 @@ def record_traffic(fetch_csv, write_csv, bench_log=None, refresh_bytes=0):
         copy = pick(tables[key], "k_refresh")
         assert len(copy) == 1
         out["calibration"][key + "_bytes_per_count"] = refresh_bytes / copy[0]
-    for span, (sub, per_step, index, files) in TRAFFIC_KERNELS.items():
+    for span, (parts, files) in TRAFFIC_KERNELS.items():
         rec = {"source_hash": source_hash(files)}
         for key in ("fetch", "write"):
-            vals = pick(tables[key], sub)
-            assert len(vals) % per_step == 0, (span, len(vals))
-            mine = vals[index::per_step]
-            rec[key + "_bytes"] = float(np.mean(mine)) * out["calibration"][key + "_bytes_per_count"]
-            rec["launches"] = len(mine)
+            rec[key + "_bytes"] = 0.0
+            for sub, per_step, index in parts:
+                vals = pick(tables[key], sub)
+                assert len(vals) % per_step == 0, (span, len(vals))
+                mine = vals[index::per_step]
+                rec[key + "_bytes"] += float(np.mean(mine)) * out["calibration"][key + "_bytes_per_count"]
+                rec["launches"] = len(mine)
         rec["bytes"] = rec["fetch_bytes"] + rec["write_bytes"]
         out["kernels"][span] = rec
     json.dump(out, open(TRAFFIC_FILE, "w"), indent=1, sort_keys=True)
@@ -211,24 +221,74 @@ def record_traffic(fetch_csv, write_csv, bench_log=None, refresh_bytes=0):
     print(json.dumps(out, indent=1, sort_keys=True))
 
 
+MFMA_SUMMARY = os.path.join(ROOT, "profiles", "gear_step_large_mfma_busy.txt")
+
+
+def record_mfma(counter_csv, n_cus=256, n_xcds=8):
+    """Matrix-pipe occupancy of the MLP's products from one `rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES
+    GRBM_GUI_ACTIVE` run of this benchmark: busy cycles summed over all SIMDs, divided by the cycles the
+    kernel was on the device (the counter adds up the XCDs' cycle counts) times the number of SIMDs."""
+    import csv
+    rows = sorted(csv.DictReader(open(counter_csv)), key=lambda r: int(r["Dispatch_Id"]))
+    by = {}
+    for r in rows:
+        by.setdefault((r["Kernel_Name"], r["Counter_Name"]), []).append(float(r["Counter_Value"]))
+
+    def pick(sub, counter):
+        hits = [v for (k, c), v in by.items() if sub in k and c == counter]
+        assert len(hits) == 1, (sub, counter)
+        return hits[0]
+
+    run = "python3 bench.py --steps 3 --warmup 1 --cpu-sample-views 0 --one-stream"
+    lines = ['# Matrix-pipe (MFMA) occupancy of the MLP products of gear_step, workload "large" (B=65536), every kernel alone',
+             "# command (from the repository root after `cd /tmp && export TMPDIR=/tmp`):",
+             f"#   rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE -d gpurun_out/pmc_mfma -o m --output-format csv -- {run}",
+             "#   python3 bench.py --record-mfma gpurun_out/pmc_mfma/m_counter_collection.csv",
+             f"# busy = SQ_VALU_MFMA_BUSY_CYCLES (summed over the {n_cus * 4} SIMDs); active = GRBM_GUI_ACTIVE / {n_xcds} (the counter",
+             f"# adds up the {n_xcds} XCDs); occupancy = busy / (active * {n_cus * 4}).  One bf16 32x32x16 MFMA keeps a pipe busy 32 cycles,",
+             "# so busy / 32 * 32768 flop is the product's flop count (checked in the last column).",
+             f"{'launch':16s} {'launches':>8s} {'busy_cycles':>14s} {'active_cycles':>14s} {'occupancy':>10s} {'GFLOP_from_busy':>16s}"]
+    for span, parts in MFMA_KERNELS.items():
+        busy = act = 0.0
+        n = 0
+        for sub, per_step, index in parts:
+            b, a = pick(sub, "SQ_VALU_MFMA_BUSY_CYCLES")[index::per_step], pick(sub, "GRBM_GUI_ACTIVE")[index::per_step]
+            busy, act, n = busy + float(np.mean(b)), act + float(np.mean(a)) / n_xcds, len(b)
+        lines.append(f"{span:16s} {n:8d} {busy:14.0f} {act:14.0f} {busy / (act * n_cus * 4):10.3f} {busy / 32 * 32768 / 1e9:16.1f}")
+    open(MFMA_SUMMARY, "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
 def cpu_baseline(wl, views):
-    """The oracle as it stands, timed on this host over one batch of `views` page views."""
-    from threadpoolctl import threadpool_info
+    """The oracle as it stands, timed on this host over one batch of `views` page views: once with its
+    matrix products on one thread, once with the BLAS thread pool as found (everything else in the
+    oracle is a plain Python loop on one thread either way)."""
+    from threadpoolctl import threadpool_info, threadpool_limits
 
     from gear_inputs import PageViewSource
     from oracle.from_workload import oracle_for
-    orc = oracle_for(wl)
     batch = PageViewSource(wl).batch(0, batch=views)
-    orc.user_emb.prefetch(batch.user_id)
-    orc.url_emb.prefetch(batch.url_id)
-    orc.dfv.prefetch(batch.img_id)
-    t0 = time.perf_counter()
-    orc.step(batch, float(np.float32(wl.lr)))
-    dt = time.perf_counter() - t0
+
+    def timed(limit):
+        orc = oracle_for(wl)
+        orc.user_emb.prefetch(batch.user_id)
+        orc.url_emb.prefetch(batch.url_id)
+        orc.dfv.prefetch(batch.img_id)
+        with threadpool_limits(limits=limit):
+            t0 = time.perf_counter()
+            orc.step(batch, float(np.float32(wl.lr)))
+            return time.perf_counter() - t0
+
+    dt1 = timed(1)
+    dtn = timed(None)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    return {"value": views / dt, "unit": "page-views/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 oracle step over one batch of {views} views drawn the way the {wl.name} workload draws "
-                      f"its batches ({dt:.1f} s; table rows materialised beforehand)"}
+    what = (f"1 oracle step over one batch of {views} views drawn the way the {wl.name} workload draws its batches "
+            "(table rows materialised beforehand)")
+    return {"value": views / dt1, "unit": "page-views/s", "cores": 1, "threads": 1, "kind": "oracle",
+            "sample": f"{what}, matrix products limited to one thread: {dt1:.1f} s",
+            "all_threads": {"value": views / dtn, "unit": "page-views/s", "cores": int(threads), "threads": int(threads),
+                            "sample": f"the same step with the BLAS thread pool as found ({threads} threads for the "
+                                      f"matrix products, the rest of the oracle on one): {dtn:.1f} s"}}
 
 
 def main():
@@ -241,6 +301,9 @@ def main():
     from gear_inputs import PageViewSource, get_workload
 
     wl = get_workload(args.workload)
+    if args.record_mfma:
+        record_mfma(args.record_mfma)
+        return
     if args.record_traffic:
         if len(args.record_traffic) not in (2, 3):
             sys.exit("--record-traffic takes FETCH_CSV WRITE_CSV [BENCH_LOG]")

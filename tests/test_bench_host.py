@@ -65,6 +65,7 @@ def test_counter_files_become_bytes_per_launch(tmp_path, monkeypatch):
     ns = "void gear::(anonymous namespace)::"
     step = [("k_gather_pool<float, unsigned short, unsigned short>(int)", 10.0), ("k_gemm_nt_dma<0>(x)", 20.0),
             ("k_gemm_nt_dma<0>(x)", 30.0), ("k_gemm_nt_dma<4>(x)", 40.0), ("k_gemm_nt_dma<3>(x)", 50.0),
+            ("k_embedding_chunks<float>(x)", 5.0), ("k_embedding_spans<float>(x)", 7.0),
             ("k_gemm_nt_dma<3>(x)", 60.0), ("k_gemm_tn_dma_batch(x)", 70.0), ("k_accumulate<unsigned short>(x)", 80.0)]
     rows = [(ns + n, v) for n, v in step] + [(ns + n, v + 2.0) for n, v in step] + [(ns + "k_refresh(x)", 1000.0)]
     _counter_csv(tmp_path / "f.csv", "FETCH_SIZE", rows)
@@ -79,9 +80,29 @@ def test_counter_files_become_bytes_per_launch(tmp_path, monkeypatch):
     assert k["dgrad_gemm_emb"]["fetch_bytes"] == 4.0 * 51.0 and k["dgrad_gemm_l0"]["fetch_bytes"] == 4.0 * 61.0
     assert k["wgrad_gemm"]["write_bytes"] == 2.0 * 142.0
     assert k["accumulate"]["bytes"] == 4.0 * 81.0 + 2.0 * 162.0 and k["accumulate"]["launches"] == 2
+    # a span of two launches is the sum of both
+    assert k["embedding_update"]["fetch_bytes"] == 4.0 * (6.0 + 8.0)
     assert "accumulate" in open(tmp_path / "traffic.txt").read()
     # a record is only reported while the kernel's source is the one it was taken on
     assert bench.recorded_traffic("accumulate") == k["accumulate"]["bytes"]
     rec["kernels"]["accumulate"]["source_hash"] = "0" * 16
     json.dump(rec, open(tmp_path / "traffic.json", "w"))
     assert bench.recorded_traffic("accumulate") is None and bench.recorded_traffic("gather_pool") is not None
+
+
+def test_mfma_counters_become_occupancy(tmp_path, monkeypatch):
+    """busy cycles over all SIMDs against the cycles on the device (the counter sums the XCDs)."""
+    monkeypatch.setattr(bench, "MFMA_SUMMARY", str(tmp_path / "mfma.txt"))
+    ns = "void gear::(anonymous namespace)::"
+    names = ["k_gemm_nt_dma<0>(x)", "k_gemm_nt_dma<0>(x)", "k_gemm_nt_dma<4>(x)", "k_gemm_nt_dma<3>(x)", "k_gemm_nt_dma<3>(x)",
+             "k_gemm_tn_dma_batch(x)"]
+    with open(tmp_path / "m.csv", "w", newline="") as f:
+        w = csv.DictWriter(f, fieldnames=["Dispatch_Id", "Kernel_Name", "Counter_Name", "Counter_Value"])
+        w.writeheader()
+        for i, n in enumerate(names):
+            w.writerow({"Dispatch_Id": i, "Kernel_Name": ns + n, "Counter_Name": "SQ_VALU_MFMA_BUSY_CYCLES", "Counter_Value": 1024.0 * 100 * (i + 1)})
+            w.writerow({"Dispatch_Id": i, "Kernel_Name": ns + n, "Counter_Name": "GRBM_GUI_ACTIVE", "Counter_Value": 8.0 * 1000})
+    bench.record_mfma(str(tmp_path / "m.csv"))
+    table = {l.split()[0]: l.split() for l in open(tmp_path / "mfma.txt") if not l.startswith("#")}
+    assert float(table["fwd_gemm_l0"][4]) == 0.1 and float(table["fwd_gemm_l1"][4]) == 0.2
+    assert float(table["wgrad_gemm"][4]) == 0.6 and table["dgrad_gemm_l0"][1] == "1"
