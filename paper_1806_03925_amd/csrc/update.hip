@@ -13,6 +13,8 @@
 // A worker is d/4 lanes, each owning one float4 column group of the row.
 #include "gear_internal.hpp"
 
+#include <type_traits>
+
 namespace gear {
 namespace {
 
@@ -98,28 +100,63 @@ k_embedding_chunks(Table users, Table urls, const float *__restrict__ dx, int F,
     row[i] = q_begin + i < q_end ? *reinterpret_cast<const float4 *>(col + (size_t)pos[i] * F)
                                  : make_float4(0.f, 0.f, 0.f, 0.f);
 
-  bool starts_here = q_begin == 0 || t.keys[q_begin - 1] != keys[0];
-  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  // running sums inside each run, in place and in order: row[i] becomes the sum of its run so far
+#pragma unroll
+  for (int i = 1; i < kChunk; ++i)
+    if (q_begin + i < q_end && keys[i] == keys[i - 1]) {
+      float4 sum = row[i - 1];
+      add4(sum, row[i]);
+      row[i] = sum;
+    }
+  // A run is complete here when it starts and ends inside the chunk; the first run may have begun in
+  // an earlier chunk, the last one may go on into the next.
+  const bool first_starts_here = q_begin == 0 || t.keys[q_begin - 1] != keys[0];
+  bool whole[kChunk];
 #pragma unroll
   for (int i = 0; i < kChunk; ++i) {
-    if (q_begin + i < q_end) {
-      add4(sum, row[i]);
-      const bool last_in_chunk = q_begin + i + 1 == q_end;
-      const bool ends_here = keys[i + 1] != keys[i];
-      if (ends_here || last_in_chunk) {
-        if (starts_here && ends_here) {
-          const size_t at = (size_t)keys[i] * d;
-          apply_row<ET>(static_cast<ET *>(t.rows) + at, t.mom.m + at, t.mom.v + at, c4, sum, opt);
-        } else {
-          float *dst = (starts_here ? t.part_last : t.part_first) + (size_t)chunk * d;
-          *reinterpret_cast<float4 *>(dst + 4 * c4) = sum;
-        }
-        sum = make_float4(0.f, 0.f, 0.f, 0.f);
-        starts_here = true;  // a run that begins after the first one starts inside this chunk
-      }
+    const bool in = q_begin + i < q_end;
+    const bool ends_here = keys[i + 1] != keys[i];
+    const bool starts_here = keys[i] != keys[0] || first_starts_here;
+    whole[i] = in && ends_here && starts_here;
+    if (in && !whole[i] && (ends_here || q_begin + i + 1 == q_end)) {
+      float *dst = (starts_here ? t.part_last : t.part_first) + (size_t)chunk * d;
+      *reinterpret_cast<float4 *>(dst + 4 * c4) = row[i];
     }
   }
+  if (opt.adam) {
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      if (whole[i]) {
+        const size_t at = (size_t)keys[i] * d;
+        apply_row<ET>(static_cast<ET *>(t.rows) + at, t.mom.m + at, t.mom.v + at, c4, row[i], opt);
+      }
+    return;
+  }
+  // Plain SGD: the rows of all complete runs are requested together, then updated and written back
+  // (ids in a sorted chunk are distinct per run, so no two of these cells are the same).  One after
+  // the other, each waiting for its own load, sixteen rows cost sixteen memory latencies.
+  using Cell = typename std::conditional<sizeof(ET) == 4, float4, uint2>::type;
+  Cell w[kChunk];
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i)
+    if (whole[i]) w[i] = reinterpret_cast<const Cell *>(static_cast<const ET *>(t.rows) + (size_t)keys[i] * d)[c4];
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i)
+    if (whole[i]) {
+      Cell *cell = reinterpret_cast<Cell *>(static_cast<ET *>(t.rows) + (size_t)keys[i] * d) + c4;
+      const float4 g = row[i];
+      if constexpr (sizeof(ET) == 4) {
+        *cell = make_float4(w[i].x - opt.lr * g.x, w[i].y - opt.lr * g.y, w[i].z - opt.lr * g.z, w[i].w - opt.lr * g.w);
+      } else {
+        const float a = __uint_as_float(w[i].x << 16) - opt.lr * g.x, b = __uint_as_float(w[i].x & 0xffff0000u) - opt.lr * g.y;
+        const float c = __uint_as_float(w[i].y << 16) - opt.lr * g.z, e = __uint_as_float(w[i].y & 0xffff0000u) - opt.lr * g.w;
+        *cell = make_uint2((uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16),
+                           (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(e) << 16));
+      }
+    }
 }
+
+constexpr int kSpanInFlight = 32;   // partials of a long run that one lane has in flight
 
 // level 2: one wavefront per chunk; if a border-crossing run starts in this chunk the wave adds
 // the run's partials in chunk order (lane = column) and writes the row
@@ -148,12 +185,12 @@ k_embedding_spans(Table users, Table urls, const int32_t *__restrict__ user_pos_
   for (int c = lane; c < d; c += kWave) {
     float sum = t.part_last[(size_t)chunk * d + c];
     int k = chunk + 1;
-    for (; k + 8 <= k_last + 1; k += 8) {     // eight partials in flight, added in order
-      float v[8];
+    for (; k + kSpanInFlight <= k_last + 1; k += kSpanInFlight) {   // added in order, requested together
+      float v[kSpanInFlight];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = t.part_first[(size_t)(k + i) * d + c];
+      for (int i = 0; i < kSpanInFlight; ++i) v[i] = t.part_first[(size_t)(k + i) * d + c];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sum += v[i];
+      for (int i = 0; i < kSpanInFlight; ++i) sum += v[i];
     }
     for (; k <= k_last; ++k) sum += t.part_first[(size_t)k * d + c];
     const size_t at = (size_t)key * d + c;
