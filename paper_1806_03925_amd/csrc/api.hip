@@ -132,7 +132,7 @@ bool make_layout(const gear_config &c, Layout *lay) {
       lay->h[l] = take(&cur, B * lay->out_dim[l] * ab);
       lay->relu_bits[l] = take(&cur, B * lay->out_dim[l] / 8);
       lay->delta[l] = take(&cur, B * lay->out_dim[l] * ab);
-      lay->splitk[l] = gemm_splitk_for(lay->out_dim[l], lay->in_dim[l], c.max_batch);
+      lay->splitk[l] = gemm_splitk_max(c.mlp_dtype, lay->out_dim[l], lay->in_dim[l], c.max_batch);
       const size_t pb = (size_t)lay->splitk[l] * wn * sizeof(float);
       if (pb > max_partial) max_partial = pb;
     }
@@ -672,7 +672,9 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
   } else {
     for (int l = L - 2; l >= 0; --l) {
-      const int splits = gemm_splitk_for(lay.out_dim[l], lay.in_dim[l], B);
+      const int splits = gemm_splitk_for(dt, lay.out_dim[l], lay.in_dim[l], B);
+      if ((size_t)splits * lay.out_dim[l] * lay.in_dim[l] * sizeof(float) > lay.wgrad_partial_bytes)
+        return GEAR_ERR_CAPACITY;  // cannot happen: sized for the largest count any batch can ask for
       GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
                                                 lay.in_dim[l], B, splits, wpart, status, s));
       GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],

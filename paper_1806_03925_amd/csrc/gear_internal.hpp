@@ -234,7 +234,8 @@ hipError_t launch_partial_sgd(const float *partial, int P, int H, float *dst, co
 // `splits` ranges is then made on the device.
 hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M, int N, int K, int splits,
                                  float *partial, const int32_t *status, hipStream_t s, const int32_t *k_dev = nullptr);
-int gemm_splitk_for(int M, int N, int K);  // wgrad split count for a [M x N] result contracted over K
+int gemm_splitk_for(int dtype, int M, int N, int K);  // wgrad split count for a [M x N] result contracted over K
+int gemm_splitk_max(int dtype, int M, int N, int K);  // the largest such count over all contraction lengths up to K
 // Several such contractions over the same K rows of bf16 operands in one launch, all with the same
 // number of k-ranges: partial_i[z][M_i x N_i].  gemm_tn_batch_splits gives that number (it looks at
 // M and N only), or 0 if the set has to go through one launch per problem.

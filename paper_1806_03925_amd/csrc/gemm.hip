@@ -1081,16 +1081,30 @@ hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, co
 
 }  // namespace
 
-// Split count of the wgrad contraction: one workgroup per CU holds a 256 x 256 tile, so aim at one
-// full round of the 256 CUs; every range keeps at least 512 rows of the batch.
-int gemm_splitk_for(int M, int N, int K) {
-  const int tiles = ((M + DM - 1) / DM) * ((N + DN - 1) / DN);
+// Split count of the wgrad contraction, never decreasing in K (a workspace sized for the largest batch
+// holds the partials of any smaller one).  bf16 with K a multiple of 32 (the DMA kernel): one
+// workgroup per CU holds a 256 x 256 tile, so aim at one full round of the 256 CUs; every range keeps
+// at least 512 rows of the batch.  Everything else goes through the register-staged kernel, whose
+// workgroup walks its range sixteen (fp32) rows at a time, each step waiting for its loads: there
+// short ranges pay, down to 128 rows, as long as the ranges of all 256 x 128 tiles fit one round.
+static int splitk_rule(bool dma, int M, int N, int K) {
+  const int tiles = dma ? ((M + DM - 1) / DM) * ((N + DN - 1) / DN) : ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   int s = 256 / tiles;
-  int cap = K / 512;
+  int cap = K / (dma ? 512 : 128);
   if (cap < 1) cap = 1;
   if (s > cap) s = cap;
   if (s > 64) s = 64;
   return s < 1 ? 1 : s;
+}
+int gemm_splitk_for(int dtype, int M, int N, int K) {
+  return splitk_rule(dtype == GEAR_BF16 && K % DK == 0, M, N, K);
+}
+// the largest count gemm_splitk_for gives for any K' <= K (which kernel a batch takes depends on K' % 32)
+int gemm_splitk_max(int dtype, int M, int N, int K) {
+  const int a = splitk_rule(false, M, N, K);
+  if (dtype != GEAR_BF16) return a;
+  const int b = splitk_rule(true, M, N, K);
+  return a > b ? a : b;
 }
 
 // Number of row-tile partials the EPI_MASK product leaves in `colpart` ([parts x N] column sums of
