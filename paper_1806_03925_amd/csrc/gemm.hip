@@ -35,6 +35,19 @@ constexpr int WM = 128, WN = 64;           // wave tile
 constexpr int TM = WM / 32, TN = WN / 32;  // MFMA tiles per wave
 constexpr int kXcds = 8;
 
+// Block geometry of the register-staged kernels: 2 x 2 wavefronts, each TM_ x TN_ MFMA tiles of 32 x 32.
+// The DMA kernels are written for the big one only (the constants above).  The smaller ones exist
+// because a product of few rows has too few 256 x 128 tiles to reach every CU.
+template <int TM_, int TN_> struct Geo {
+  static constexpr int TM = TM_, TN = TN_, WM = 32 * TM_, WN = 32 * TN_, BM = 2 * WM, BN = 2 * WN;
+};
+using GeoBig = Geo<4, 2>;    // 256 x 128
+using GeoMid = Geo<2, 2>;    // 128 x 128
+using GeoSmall = Geo<1, 1>;  //  64 x  64
+#define GEAR_GEO(G) \
+  constexpr int TM = G::TM, TN = G::TN, WM = G::WM, WN = G::WN, BM = G::BM, BN = G::BN; \
+  (void)TM, (void)TN, (void)WM, (void)WN, (void)BM, (void)BN
+
 template <typename T> struct Tile;
 template <> struct Tile<bf16_t> {
   static constexpr int BK = 64, LDK = 72, VEC = 8;
@@ -171,8 +184,10 @@ struct StageTNf32 {
 };
 
 // ---- LDS -> MFMA -----------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ void mma_tile(f32x16_v (&acc)[TM][TN], const T *As, const T *Bs, int wm, int wn, int lane) {
+template <typename T, typename G = GeoBig>
+__device__ __forceinline__ void mma_tile(f32x16_v (&acc)[G::TM][G::TN], const T *As, const T *Bs, int wm, int wn,
+                                         int lane) {
+  GEAR_GEO(G);
   constexpr int LDK = Tile<T>::LDK, BK = Tile<T>::BK;
   const int r = lane & 31, g = lane >> 5;
   if constexpr (sizeof(T) == 2) {
@@ -209,10 +224,11 @@ __device__ __forceinline__ void mma_tile(f32x16_v (&acc)[TM][TN], const T *As, c
 
 // Accumulator element e of a 32x32 tile sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
 // fp32 results are stored straight from that layout (a half-wave covers 128 contiguous bytes).
-template <typename T, int EPI>
-__device__ __forceinline__ void epilogue_direct(const f32x16_v (&acc)[TM][TN], int m0, int n0, int wm, int wn,
+template <typename T, int EPI, typename G = GeoBig>
+__device__ __forceinline__ void epilogue_direct(const f32x16_v (&acc)[G::TM][G::TN], int m0, int n0, int wm, int wn,
                                                 int lane, int M, int N, const float *__restrict__ bias,
                                                 const T *__restrict__ aux, void *__restrict__ out, int split = 0) {
+  GEAR_GEO(G);
   const int c = lane & 31, g = lane >> 5;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -249,10 +265,12 @@ __device__ __forceinline__ void epilogue_direct(const f32x16_v (&acc)[TM][TN], i
 // bf16 results: each wave parks 64 rows x 64 columns at a time in its own LDS patch, then every lane
 // moves 16 contiguous bytes (eight lanes per 128-byte row piece); the ReLU mask of the dgrad is read
 // with the same 16-byte pattern.
-template <int EPI>
-__device__ __forceinline__ void epilogue_bf16(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
+template <int EPI, typename G = GeoBig>
+__device__ __forceinline__ void epilogue_bf16(const f32x16_v (&acc)[G::TM][G::TN], bf16_t *patch, int m0, int n0, int wm,
                                               int wn, int lane, int M, int N, const float *__restrict__ bias,
                                               const bf16_t *__restrict__ aux, bf16_t *__restrict__ out) {
+  GEAR_GEO(G);
+  static_assert(G::TM % 2 == 0 && G::TN == 2, "the patch holds 64 rows x 64 columns of a wave's tile");
   constexpr int LDC = WN + 8;  // bf16 elements per patch row
   const int c = lane & 31, g = lane >> 5;
 #pragma unroll
@@ -877,13 +895,16 @@ k_gemm_tn_dma_batch(TnBatchArgs args, int K, int k_chunk, const int32_t *__restr
 }
 
 // ---- kernels ---------------------------------------------------------------------------------------
-constexpr size_t lds_bytes(size_t elem, int ldk) { return (size_t)(BM + BN) * ldk * elem; }
+template <typename G = GeoBig> constexpr size_t lds_bytes(size_t elem, int ldk) {
+  return (size_t)(G::BM + G::BN) * ldk * elem;
+}
 
-template <typename T, int EPI>
+template <typename T, int EPI, typename G>
 __global__ void __launch_bounds__(THREADS)
 k_gemm_nt(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K, const float *__restrict__ bias,
           const T *__restrict__ aux, void *__restrict__ out, int split, const int32_t *__restrict__ status) {
   if (*status != 0) return;
+  GEAR_GEO(G);
   constexpr int BK = Tile<T>::BK, LDK = Tile<T>::LDK;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   T *As = reinterpret_cast<T *>(smem);
@@ -915,15 +936,15 @@ k_gemm_nt(const T *__restrict__ A, const T *__restrict__ B, int M, int N, int K,
       sa.load(A, K, m0, M, k0 + BK, K, tid);
       sb.load(B, K, n0, N, k0 + BK, K, tid);
     }
-    mma_tile<T>(acc, As, Bs, wm, wn, lane);
+    mma_tile<T, G>(acc, As, Bs, wm, wn, lane);
     __syncthreads();
   }
-  if constexpr (sizeof(T) == 2 && EPI != EPI_F32 && EPI != EPI_DX) {
+  if constexpr (sizeof(T) == 2 && EPI != EPI_F32 && EPI != EPI_DX && G::TM % 2 == 0 && G::TN == 2) {
     bf16_t *patch = reinterpret_cast<bf16_t *>(smem) + wave * 64 * (WN + 8);
-    epilogue_bf16<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, reinterpret_cast<const bf16_t *>(aux),
-                       static_cast<bf16_t *>(out));
+    epilogue_bf16<EPI, G>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, reinterpret_cast<const bf16_t *>(aux),
+                          static_cast<bf16_t *>(out));
   } else {
-    epilogue_direct<T, EPI>(acc, m0, n0, wm, wn, lane, M, N, bias, aux, out, split);
+    epilogue_direct<T, EPI, G>(acc, m0, n0, wm, wn, lane, M, N, bias, aux, out, split);
   }
 }
 
@@ -1042,7 +1063,6 @@ __global__ void __launch_bounds__(256) k_splitk_sgd_batch(SplitkBatchArgs args, 
 template <typename T>
 hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, const float *bias, const void *aux,
                   void *out, int split, float *colpart, uint8_t *relu_bits, const int32_t *status, hipStream_t s) {
-  const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
   if constexpr (sizeof(T) == 2) {
     if (K % DK == 0) {
       const dim3 grid(((M + DM - 1) / DM) * ((N + DN - 1) / DN));
@@ -1063,18 +1083,30 @@ hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, co
       return hipGetLastError();
     }
   }
-  const size_t smem = lds_bytes(sizeof(T), Tile<T>::LDK);
-#define GEAR_NT(E)                                                                                                  \
-  hipLaunchKernelGGL((k_gemm_nt<T, E>), grid, dim3(THREADS), smem, s, (const T *)A, (const T *)B, M, N, K, bias,    \
+  // the largest geometry that still gives every CU a tile (else the smallest)
+#define GEAR_NT_G(E, G)                                                                                             \
+  hipLaunchKernelGGL((k_gemm_nt<T, E, G>), dim3(((M + G::BM - 1) / G::BM) * ((N + G::BN - 1) / G::BN)), dim3(THREADS), \
+                     lds_bytes<G>(sizeof(T), Tile<T>::LDK), s, (const T *)A, (const T *)B, M, N, K, bias,          \
                      (const T *)aux, out, split, status)
+#define GEAR_NT(E)                                                                        \
+  {                                                                                       \
+    if (tiles_of(GeoBig::BM, GeoBig::BN) >= 256)                                          \
+      GEAR_NT_G(E, GeoBig);                                                               \
+    else if (tiles_of(GeoMid::BM, GeoMid::BN) >= 256)                                     \
+      GEAR_NT_G(E, GeoMid);                                                               \
+    else                                                                                  \
+      GEAR_NT_G(E, GeoSmall);                                                             \
+  }
+  auto tiles_of = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
   if (epi == EPI_BIAS_RELU)
-    GEAR_NT(EPI_BIAS_RELU);
+    GEAR_NT(EPI_BIAS_RELU)
   else if (epi == EPI_MASK)
-    GEAR_NT(EPI_MASK);
+    GEAR_NT(EPI_MASK)
   else if (epi == EPI_DX)
-    GEAR_NT(EPI_DX);
+    GEAR_NT(EPI_DX)
   else
-    GEAR_NT(EPI_F32);
+    GEAR_NT(EPI_F32)
+#undef GEAR_NT_G
 #undef GEAR_NT
   return hipGetLastError();
 }
@@ -1179,10 +1211,10 @@ hipError_t launch_gemm_tn_splitk(int dtype, const void *A, const void *B, int M,
   }
   const dim3 grid(((M + BM - 1) / BM) * ((N + BN - 1) / BN), 1, splits);
   if (dtype == GEAR_BF16)
-    hipLaunchKernelGGL(k_gemm_tn<bf16_t>, grid, dim3(THREADS), lds_bytes(2, Tile<bf16_t>::LDK), s, (const bf16_t *)A,
+    hipLaunchKernelGGL(k_gemm_tn<bf16_t>, grid, dim3(THREADS), lds_bytes<>(2, Tile<bf16_t>::LDK), s, (const bf16_t *)A,
                        (const bf16_t *)B, M, N, K, k_chunk, partial, status, k_dev);
   else
-    hipLaunchKernelGGL(k_gemm_tn<float>, grid, dim3(THREADS), lds_bytes(4, Tile<float>::LDK), s, (const float *)A,
+    hipLaunchKernelGGL(k_gemm_tn<float>, grid, dim3(THREADS), lds_bytes<>(4, Tile<float>::LDK), s, (const float *)A,
                        (const float *)B, M, N, K, k_chunk, partial, status, k_dev);
   return hipGetLastError();
 }

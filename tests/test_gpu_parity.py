@@ -932,7 +932,9 @@ def test_refresh_overwrites_rows_and_nothing_else():
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("M,N,K", [(300, 136, 200), (1, 8, 8), (517, 1152, 1024), (2048, 256, 64),
                                    # more tiles than compute units (a workgroup walks several), ragged in both directions
-                                   (70000, 328, 160), (66000, 520, 96)])
+                                   (70000, 328, 160), (66000, 520, 96),
+                                   # too few 256 x 128 tiles for every compute unit: the 128 x 128 geometry
+                                   (16500, 264, 200)])
 def test_gemm_forms_against_fp32_matmul(dtype, M, N, K):
     """Both forms against a plain fp32/fp64 matmul of the same operands (ragged tiles included)."""
     td = torch.bfloat16 if dtype == "bf16" else torch.float32
