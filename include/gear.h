@@ -12,7 +12,7 @@
  *
  * This library is that per-step work.  All pointers named "device" are device
  * memory owned by the caller; the library allocates no device memory and keeps
- * no state between calls except one helper stream and two events per device,
+ * no state between calls except one helper stream and three events per device,
  * created at the first gear_step (default priority; part of a step runs on it,
  * forked from and joined back into the caller's stream).  Calls enqueue their
  * kernels on the given hipStream_t (passed as void*) and return without

@@ -222,12 +222,12 @@ void *static_scratch() {
 }
 }  // namespace
 
-// One helper stream and two events per device, created on first use and kept for the life of the
+// One helper stream and three events per device, created on first use and kept for the life of the
 // process: the integer grouping of a step runs beside its gather and forward pass.
 namespace {
 struct SideLane {
   hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, checked = nullptr;
   bool ready = false;
   std::mutex busy;  // held while a step enqueues: two host threads never interleave their forks and joins
 };
@@ -247,11 +247,13 @@ SideLane *side_lane() {
   SideLane &l = g_side[dev];
   if (!l.ready) {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, checked = nullptr;
     bool ok = hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&checked, hipEventDisableTiming) == hipSuccess;
     if (!ok) {
+      if (checked) (void)hipEventDestroy(checked);
       if (join) (void)hipEventDestroy(join);
       if (fork) (void)hipEventDestroy(fork);
       if (stream) (void)hipStreamDestroy(stream);
@@ -260,13 +262,14 @@ SideLane *side_lane() {
     l.stream = stream;
     l.fork = fork;
     l.join = join;
+    l.checked = checked;
     l.ready = true;
   }
   return &l;
 }
 
 // A step's use of the helper lane.  Holds the lane for the whole enqueue, so that steps issued from
-// several host threads on one device use the lane's two events one after the other, and makes sure
+// several host threads on one device use the lane's events one after the other, and makes sure
 // that whatever was forked to the helper stream is joined back into the caller's stream however the
 // enqueue ends: after an early return (a failed launch) the next call on the caller's stream must
 // not run beside kernels this call left on the helper stream.
@@ -295,6 +298,9 @@ class LaneScope {
   }
   // marks the point of the helper stream that a later wait() refers to
   hipError_t mark() { return side_ ? hipEventRecord(side_->join, side_->stream) : hipSuccess; }
+  // the same for the end of the helper's first part (ids checked, plan made): the status word is final
+  hipError_t mark_checked() { return side_ ? hipEventRecord(side_->checked, side_->stream) : hipSuccess; }
+  hipError_t wait_checked() { return side_ ? hipStreamWaitEvent(s_, side_->checked, 0) : hipSuccess; }
   // the caller's stream continues after the last mark(); final = nothing is given to the helper after it
   hipError_t wait(bool final) {
     if (!side_) return hipSuccess;
@@ -531,7 +537,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                              out->n_ready, status, s));
     GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
   }
-  GEAR_HIP(lane.mark());
+  GEAR_HIP(lane.mark_checked());
 
   // forward
   void *x = ws + lay.x;
@@ -554,11 +560,11 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
                                      ws + lay.h[l], 0, nullptr, relu_bits[l], status, s));
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
-  // Until its first kernel that changes caller state, the caller's stream writes the workspace only
-  // and need not know whether the ids were in range or the ready list fits.  With one launch for
-  // all weight gradients that kernel is the last one of the step, behind the final join; otherwise
-  // the stream waits here for the helper's first part, so that the status word is final.
-  if (batch_splits == 0) GEAR_HIP(lane.wait(false));
+  // Until its first kernel that changes caller state (the first SGD on a hidden layer's weights), the
+  // caller's stream writes the workspace only and need not know whether the ids were in range or the
+  // ready list fits.  With one launch for all weight gradients that kernel is the last one of the step,
+  // behind the final join; otherwise the stream waits, just before it, for the helper's first part, so
+  // that the status word is final.
   GEAR_RUN("logit_loss", launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1],
                                            b->label, B, lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2],
                                            (float *)(ws + lay.loss_partial), status, s));
@@ -677,6 +683,7 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
         return GEAR_ERR_CAPACITY;  // cannot happen: sized for the largest count any batch can ask for
       GEAR_RUN(kWgrad[l], launch_gemm_tn_splitk(dt, ws + lay.delta[l], l == 0 ? x : ws + lay.h[l - 1], lay.out_dim[l],
                                                 lay.in_dim[l], B, splits, wpart, status, s));
+      if (l == L - 2) GEAR_HIP(lane.wait_checked());
       GEAR_RUN("splitk_sgd", launch_splitk_sgd(wpart, splits, (int64_t)lay.out_dim[l] * lay.in_dim[l],
                                                t->mlp_params + lay.w_off[l], opt, moments_at(mom_mlp, lay.w_off[l]),
                                                status, s));
