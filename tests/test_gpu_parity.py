@@ -756,6 +756,59 @@ def test_one_stream_and_two_streams_give_the_same_bits(name, batch):
         assert torch.equal(a, b)
 
 
+def test_two_host_threads_stepping_their_own_states_on_one_device():
+    """The entry points may be called from several host threads.  Two threads, each with its own state,
+    workspace and stream, step at the same time; a step forks to and joins from the device's one helper
+    stream with a fixed set of events, so their enqueues must not interleave.  Every thread must end
+    with exactly the bits it gets when it runs alone."""
+    import threading
+    wls = [get_workload("small").scaled(n_users=50_000, n_urls=1 << 15, n_images=4_000, M=4),
+           get_workload("bf16").scaled(n_users=50_000, n_urls=1 << 15, n_images=4_000, M=4)]
+    batches, steps = [1200, 1504], 6
+
+    def run(i, stream, out, barrier=None):
+        wl = wls[i]
+        with torch.cuda.stream(stream):
+            cfg, st, _ = make_pair(wl, max_batch=batches[i])
+            src = PageViewSource(wl)
+            dev = [g.DeviceBatch.from_host(src.batch(t, batch=batches[i])) for t in range(steps)]
+            stream.synchronize()
+            if barrier is not None:
+                barrier.wait()
+            for t in range(steps):
+                g.gear_step(st, dev[t], wl.M, 0.5)
+            stream.synchronize()
+            assert int(st.status.item()) == 0
+            n = int(st.n_ready.item())
+            out[i] = [x.clone() for x in (st.loss, st.ready_ids[:n], st.ready_grads[:n], st.grad_accum, st.counts,
+                                          st.user_emb, st.url_emb, st.mlp_params)]
+
+    alone, together = {}, {}
+    for i in range(2):
+        run(i, torch.cuda.Stream(), alone)
+    barrier = threading.Barrier(2)
+    errors = []
+
+    def guarded(i, stream):
+        try:
+            run(i, stream, together, barrier)
+        except BaseException as e:      # surfaces in the main thread below
+            errors.append(e)
+            barrier.abort()
+
+    threads = [threading.Thread(target=guarded, args=(i, torch.cuda.Stream())) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not errors, errors
+    assert all(not t.is_alive() for t in threads)
+    torch.cuda.synchronize()
+    for i in range(2):
+        for a, b in zip(alone[i], together[i]):
+            assert torch.equal(a, b), i
+
+
 # ------------------------------------------------------------------ edge cases
 def test_empty_views_duplicates_and_single_view():
     wl = get_workload("tiny").scaled(M=2)
