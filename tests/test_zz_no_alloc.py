@@ -61,3 +61,52 @@ def test_static_scratch_rejects_a_configuration_that_does_not_fit():
     torch.cuda.synchronize()
     for a, c in zip(before, (st.user_emb, st.mlp_params, st.grad_accum, st.counts)):
         assert torch.equal(a, c)
+
+
+def test_static_step_replays_from_a_graph():
+    """The step on the static scratch array launches everything on one stream and allocates nothing, so
+    a caller can record it into a graph.  A graph fixes the batch's shape (B and the number of
+    occurrences are launch arguments), so the workload here has one image per view; the batch's
+    contents change between replays through the same device buffers.  Each replay, with eager work and
+    synchronisations in between, must leave exactly what the eager step leaves."""
+    import paper_1806_03925_amd as g
+    wl = get_workload("epoch").scaled(batch=600, n_images=1800, M=2)
+    src = PageViewSource(wl)
+
+    def state():
+        st = g.GearState(g.config_for(wl), debug=False)
+        g.gear_init_tables(st)
+        g.gear_fill_normal(st.dfv_cache, wl.n_images, wl.dfv_dim, wl.seed, 3, wl.dfv_std)
+        return st
+
+    ref, dut = state(), state()
+    first = g.DeviceBatch.from_host(src.batch(0))
+    slot = g.DeviceBatch(*(t.clone() for t in (first.user_id, first.url_id, first.img_off, first.img_id, first.label)))
+    torch.cuda.synchronize()
+    # warm-up outside the graph on a scratch state (first-use set-up must not happen under capture)
+    g.gear_step_static(state(), slot, wl.M, wl.lr)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g.gear_step_static(dut, slot, wl.M, wl.lr)
+    torch.cuda.synchronize()
+    before = [t.clone() for t in (dut.counts, dut.grad_accum, dut.user_emb, dut.mlp_params)]
+    for a, b in zip(before, (ref.counts, ref.grad_accum, ref.user_emb, ref.mlp_params)):
+        assert torch.equal(a, b)                        # recording ran nothing
+    for step in range(5):
+        b = g.DeviceBatch.from_host(src.batch(step))
+        assert b.nnz == slot.nnz and b.B == slot.B
+        for dst, s in zip((slot.user_id, slot.url_id, slot.img_off, slot.img_id, slot.label),
+                          (b.user_id, b.url_id, b.img_off, b.img_id, b.label)):
+            dst.copy_(s)
+        graph.replay()
+        g.gear_step(ref, b, wl.M, wl.lr)
+        torch.cuda.synchronize()
+        n = int(ref.n_ready.item())
+        assert int(dut.status.item()) == 0 and int(dut.n_ready.item()) == n, step
+        for a, c in zip((ref.loss, ref.ready_ids[:n], ref.ready_grads[:n], ref.grad_accum, ref.counts, ref.user_emb,
+                         ref.url_emb, ref.mlp_params),
+                        (dut.loss, dut.ready_ids[:n], dut.ready_grads[:n], dut.grad_accum, dut.counts, dut.user_emb,
+                         dut.url_emb, dut.mlp_params)):
+            assert torch.equal(a, c), step
+    assert int(ref.counts.sum().item()) == 5 * 600
