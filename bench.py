@@ -426,7 +426,7 @@ def main():
     st.one_stream = args.one_stream
 
     # the workload's periodic full DFV refresh (new vectors stand in for a Dense-Part inference pass)
-    refresh_ms, copy_gbs, dense_refresh_ms = 0.0, None, None
+    refresh_ms, copy_gbs, dense_refresh_ms, row_copy_gbs = 0.0, None, None, None
     refresh_every = 0 if expiry is not None else wl.refresh_every   # expiry mode replaces the periodic full refresh
     if wl.refresh_every:
         fresh = torch.empty_like(st.dfv_cache)
@@ -451,7 +451,21 @@ def main():
         refresh_ms = e0.elapsed_time(e1)
         # the refresh is a plain copy of the whole cache: what this device's HBM sustains in practice
         copy_gbs = 2.0 * wl.n_images * wl.dfv_dim * BYTES[wl.dfv_dtype] / (refresh_ms * 1e-3) / 1e9
-        del fresh
+        # ... and the same kernel over as many distinct random rows as a batch has occurrences: what moving whole
+        # rows with no reuse can reach (rows read in order from the fresh table, written to random rows of the cache)
+        n_rows = min(wl.max_nnz // 2, wl.n_images // 2)
+        ids = torch.randperm(wl.n_images, device="cuda")[:n_rows].to(torch.int32)
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        rows = fresh[:n_rows]                                # the call takes its row count from this argument
+        g.gear_refresh_dfv(st, ids, rows)                    # once untimed
+        torch.cuda.synchronize()
+        r0.record()
+        for _ in range(5):
+            g.gear_refresh_dfv(st, ids, rows)
+        r1.record()
+        torch.cuda.synchronize()
+        row_copy_gbs = 2.0 * n_rows * wl.dfv_dim * BYTES[wl.dfv_dtype] / (r0.elapsed_time(r1) / 5 * 1e-3) / 1e9
+        del fresh, rows
 
     per_refresh = dense_refresh_ms if dense_refresh_ms is not None else refresh_ms
     ms_per_step = loop_ms / K + (per_refresh / refresh_every if refresh_every else 0.0)
@@ -495,7 +509,8 @@ def main():
                    "expired_rows_per_step": refreshed_per_step,
                    "loop_ms_per_step": loop_ms / K, "profiled_ms_per_step": sum(r["ms_per_step"] for r in kernels),
                    "step_ms_p10_p50_p90": [float(np.percentile(step_ms, q)) for q in (10, 50, 90)],
-                   "hbm_copy_GBs": copy_gbs, "timed_steps_on_one_stream": bool(args.one_stream)},
+                   "hbm_copy_GBs": copy_gbs, "hbm_random_row_copy_GBs": row_copy_gbs,
+                   "timed_steps_on_one_stream": bool(args.one_stream)},
         "loss": loss,
         "roofline": roofline,
         "kernels": kernels,
