@@ -407,6 +407,20 @@ def main():
     for i in range(it - K, it):
         model.step(host[i % pool])
 
+    # a caller that waits for every step before it issues the next (the host is never ahead of the
+    # device): host wall clock from the call to the end of the wait
+    n_waited = min(K, 10)
+    waited = []
+    for i in range(n_waited):
+        torch.cuda.synchronize()
+        t_call = time.perf_counter()
+        one_step(it)
+        torch.cuda.synchronize()
+        waited.append((time.perf_counter() - t_call) * 1e3)
+        it += 1
+    for i in range(it - n_waited, it):
+        model.step(host[i % pool])
+
     # per-kernel durations: the same steps again with HIP events around every launch, all on one
     # stream, so that a duration is that of the kernel alone (in the timed steps above, parts of a
     # step run side by side on two streams and share the device)
@@ -509,6 +523,7 @@ def main():
                    "expired_rows_per_step": refreshed_per_step,
                    "loop_ms_per_step": loop_ms / K, "profiled_ms_per_step": sum(r["ms_per_step"] for r in kernels),
                    "step_ms_p10_p50_p90": [float(np.percentile(step_ms, q)) for q in (10, 50, 90)],
+                   "waited_step_ms_median": float(np.median(waited)),
                    "hbm_copy_GBs": copy_gbs, "hbm_random_row_copy_GBs": row_copy_gbs,
                    "timed_steps_on_one_stream": bool(args.one_stream)},
         "loss": loss,

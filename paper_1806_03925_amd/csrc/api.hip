@@ -529,16 +529,6 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     }
     GEAR_RUN("cast_weights", launch_cast_weights(L, cw, lay.out_dim, lay.in_dim, dt, cwc, cwct, status, s));
   }
-  {
-    hipStream_t s = helper;  // the launches of this block go to the helper stream
-    GEAR_RUN("validate", launch_validate(*cfg, *b, occ_view, status, s));
-    GEAR_RUN("group_ids", launch_group(gb, status, s));
-    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap,
-                                             out->n_ready, status, s));
-    GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
-  }
-  GEAR_HIP(lane.mark_checked());
-
   // forward
   void *x = ws + lay.x;
   // the weight-gradient products of the hidden layers, and whether they go out as one launch
@@ -559,12 +549,24 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
     GEAR_RUN(kFwd[l], launch_gemm_nt(dt, l == 0 ? x : ws + lay.h[l - 1], ws + lay.wc[l], B, lay.out_dim[l],
                                      lay.in_dim[l], EPI_BIAS_RELU, t->mlp_params + lay.b_off[l], nullptr,
                                      ws + lay.h[l], 0, nullptr, relu_bits[l], status, s));
+  // The helper stream's launches are issued after the forward pass's: where the host is not ahead of the
+  // device (a caller that waits for every step), the gather then starts as soon as the step does, not
+  // after the host has issued the grouping's many small launches.
+  {
+    hipStream_t s = helper;  // the launches of this block go to the helper stream
+    GEAR_RUN("validate", launch_validate(*cfg, *b, occ_view, status, s));
+    GEAR_RUN("group_ids", launch_group(gb, status, s));
+    GEAR_RUN("accum_plan", launch_accum_plan(gb.p[2], plan, occ_view, b->img_off, counts, M, out->ready_cap,
+                                             out->n_ready, status, s));
+    GEAR_RUN("count_update", launch_count_update(gb.p[2], counts, status, s));
+  }
+  GEAR_HIP(lane.mark_checked());
+
   float *logits = (float *)(ws + lay.logits), *dz = (float *)(ws + lay.dz);
   // Until its first kernel that changes caller state (the first SGD on a hidden layer's weights), the
   // caller's stream writes the workspace only and need not know whether the ids were in range or the
-  // ready list fits.  With one launch for all weight gradients that kernel is the last one of the step,
-  // behind the final join; otherwise the stream waits, just before it, for the helper's first part, so
-  // that the status word is final.
+  // ready list fits.  Just before that kernel the stream waits for the helper's first part, so that the
+  // status word is final.
   GEAR_RUN("logit_loss", launch_logit_loss(dt, ws + lay.h[L - 2], ws + lay.wc[L - 1], t->mlp_params + lay.b_off[L - 1],
                                            b->label, B, lay.in_dim[L - 1], logits, dz, ws + lay.delta[L - 2],
                                            (float *)(ws + lay.loss_partial), status, s));
@@ -671,11 +673,14 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
       sp[i] = SplitkProblem{wp[i].partial, t->mlp_params + lay.w_off[l], moments_at(mom_mlp, lay.w_off[l]),
                             (int64_t)wp[i].M * wp[i].N};
     }
-    // the step's work on the helper stream ends here; the sums of the partials and the SGD follow it
-    // (they would not get onto the device before the bookkeeping's workgroups are all placed anyway)
+    // The sums of the partials and the SGD change caller state, so the status word has to be final: the
+    // stream waits for the helper's first part (long done by now), not for the bookkeeping.  They do not
+    // get onto the device before the bookkeeping's workgroups have all been placed, which is near its end,
+    // but the join that ends the step then costs nothing more.
+    GEAR_HIP(lane.wait_checked());
+    GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
     GEAR_HIP(lane.wait(true));
     joined = true;
-    GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
   } else {
     for (int l = L - 2; l >= 0; --l) {
       const int splits = gemm_splitk_for(dt, lay.out_dim[l], lay.in_dim[l], B);
