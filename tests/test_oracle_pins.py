@@ -471,6 +471,24 @@ def test_branch_choice_is_taken_only_within_rounding_distance_of_the_kink():
     assert none.refused_units == 1 and np.array_equal(none.dx, own.dx)
 
 
+def test_a_unit_switched_on_below_zero_passes_zero_forward_and_its_gradient_backward():
+    """A chosen "on" at a unit whose own pre-activation is just below zero: ReLU's value there is 0, not the
+    negative pre-activation, so the logit is that of the own pass; backward the unit counts as active, so
+    dLoss/dx gains its term.  a = [-2^-20, 1], logit weights [4, -1]."""
+    W1 = np.array([[-2.0 ** -20, 0.0, 0.0], [0.0, 0.0, 1.0]])
+    def build():
+        return GearOracle(RowStore(1, 1, "f64", dense=np.array([[1.0]])), RowStore(1, 1, "f64", dense=np.array([[0.0]])),
+                          RowStore(1, 1, "f64", dense=np.array([[1.0]])),
+                          [(W1, np.zeros(2)), (np.array([[4.0, -1.0]]), np.array([1.0]))], 1, Precision.exact())
+    batch = batch_from_lists([0], [0], [[0]], [1])
+    own = build().step(batch, 0.0)
+    on = build().step(batch, 0.0, relu_choice=[np.array([[True, True]])], kink_tol=1e-5)
+    assert on.chosen_units == 1 and own.dx[0, 0] == 0.0
+    assert on.logits[0] == own.logits[0] == 0.0 and on.loss == own.loss          # z = 4 * 0 - 1 * 1 + 1
+    dz = 0.5 - 1.0                                                               # sigmoid(0) - y, one view
+    assert on.dx[0, 0] == dz * 4.0 * W1[0, 0] and np.array_equal(on.dx[0, 1:], own.dx[0, 1:])
+
+
 def test_branch_choice_decides_what_the_step_applies():
     """The state after a step follows the chosen branches (weights, rows, stored gradients), so that two
     arithmetics that agree on the branches stay together over many steps."""
@@ -679,3 +697,17 @@ def test_dense_standin_infer_rounds_to_the_cache_type():
     assert np.allclose(rows[1], dense.wd @ dense.raw[0], rtol=2 ** -8)
     with pytest.raises(ValueError):
         dense.infer([5])
+
+
+def test_dense_standin_weights_stay_fp32_values():
+    """The stand-in's weights are fp32 masters: one rounding after a backward pass over a whole ready list,
+    none between its emissions.  Wd = [[1]], raw = [[1], [1]], two emissions of -2^-24 at lr 1: each alone is
+    half a unit in the last place of 1 and would round back to 1 (ties to even); together they are one."""
+    from oracle.dense_standin import DenseStandIn
+    dense = DenseStandIn(np.array([[1.0], [1.0]]), np.array([[1.0]]), "f32")
+    g = np.array([[-2.0 ** -24], [-2.0 ** -24]])
+    dense.backward([0, 1], g, 1.0)
+    assert dense.wd[0, 0] == 1.0 + 2.0 ** -23 == float(np.float32(dense.wd[0, 0]))
+    dense = DenseStandIn(np.array([[1.0], [1.0]]), np.array([[1.0]]), "f32")
+    dense.backward([0], g[:1], 1.0)
+    assert dense.wd[0, 0] == 1.0                                  # 1 + 2^-24 is not an fp32 number
