@@ -158,7 +158,7 @@ def write_traffic_summary(rec, refresh_bytes, bench_log=None):
         "bytes per count (the counter's KiB unit sees half of the 128-byte reads)",
         f"#   WRITE_SIZE reads {refresh_bytes / cal['write_bytes_per_count']:.0f} for it -> {cal['write_bytes_per_count']:.1f} "
         "bytes per count",
-        f"# averages over {k['accumulate']['launches']} launches (the first steps after initialisation, every kernel alone "
+        f"# averages over the last {k['accumulate']['launches']} launches of a run (its launch-by-launch pass, every kernel alone "
         "on one stream); the machine-readable copy is profiles/traffic.json",
         f"{'launch':16s} {'fetch_MB':>10s} {'write_MB':>10s} {'total_MB':>10s}",
     ]
@@ -171,7 +171,7 @@ def write_traffic_summary(rec, refresh_bytes, bench_log=None):
                      f"accumulate {alg['accumulate'] / 1e6:.1f} MB, gather_pool {alg['gather_pool'] / 1e6:.1f} MB, "
                      f"embedding_update {alg['embedding_update'] / 1e6:.1f} MB")
         lines.append("# (accumulate's grows with the step number, as more images carry a partial sum that has to be read: "
-                     "about 850 MB around step 100)")
+                     "530 MB in the first step after initialisation, 720 MB in the eighth, about 850 MB around step 100)")
     lines += ["# the excess is re-reads of dLoss/dx rows (accumulate: one row per occurrence, 4.5 per view) and of cached "
               "DFV rows (gather) that miss in L2.",
               "# dgrad_gemm_l1 reads the 8 MB sign bitmap of the first hidden layer instead of its 134 MB of activations."]
@@ -198,11 +198,17 @@ def record_traffic(fetch_csv, write_csv, bench_log=None, refresh_bytes=0):
         return hits[0]
 
     out = {"unit": "bytes per launch", "calibration": {}, "kernels": {}}
+    # with the run's own line at hand: only the launches of its last pass (the `steps` steps that are timed launch
+    # by launch and whose algorithmic bytes the line carries), so that both figures are of the same steps
+    last = None
+    if bench_log:
+        last = int(json.loads([l for l in open(bench_log) if l.startswith("{")][-1])["steps"])
     tables = {}
     for key, path, counter in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
         tables[key] = per_kernel(path, counter)
         copy = pick(tables[key], "k_refresh")
-        assert len(copy) == 1
+        # the first launch of that kernel is the full refresh; the later ones (the random-row probe) are smaller
+        assert len(copy) >= 1 and copy[0] == max(copy)
         out["calibration"][key + "_bytes_per_count"] = refresh_bytes / copy[0]
     for span, (parts, files) in TRAFFIC_KERNELS.items():
         rec = {"source_hash": source_hash(files)}
@@ -212,6 +218,8 @@ def record_traffic(fetch_csv, write_csv, bench_log=None, refresh_bytes=0):
                 vals = pick(tables[key], sub)
                 assert len(vals) % per_step == 0, (span, len(vals))
                 mine = vals[index::per_step]
+                if last:
+                    mine = mine[-last:]
                 rec[key + "_bytes"] += float(np.mean(mine)) * out["calibration"][key + "_bytes_per_count"]
                 rec["launches"] = len(mine)
         rec["bytes"] = rec["fetch_bytes"] + rec["write_bytes"]
@@ -323,7 +331,8 @@ def main():
 
     K, W = args.steps, args.warmup
     src = PageViewSource(wl)
-    pool = min(W + 3 * K, 160)
+    # a batch of its own for every step (warm-up, timed, spread, waited, launch by launch), up to 160 (320 MB on the device)
+    pool = min(W + 3 * K + min(K, 10), 160)
     host = [src.batch(i) for i in range(pool)]
     dev = [g.DeviceBatch.from_host(b) for b in host]
     lr = float(wl.lr)
