@@ -674,9 +674,9 @@ gear_status gear_step_adam(const gear_config *cfg, const gear_batch *b, gear_tab
                             (int64_t)wp[i].M * wp[i].N};
     }
     // The sums of the partials and the SGD change caller state, so the status word has to be final: the
-    // stream waits for the helper's first part (long done by now), not for the bookkeeping.  They do not
-    // get onto the device before the bookkeeping's workgroups have all been placed, which is near its end,
-    // but the join that ends the step then costs nothing more.
+    // stream waits for the helper's first part (long done by now), not for the bookkeeping.  Their
+    // workgroups get onto the device as the bookkeeping's leave room and are done before it is, so the
+    // step ends with the bookkeeping and the join.
     GEAR_HIP(lane.wait_checked());
     GEAR_RUN("splitk_sgd", launch_splitk_sgd_batch(sp, n_wp, batch_splits, opt, status, s));
     GEAR_HIP(lane.wait(true));
