@@ -107,15 +107,16 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 # span -> (parts, source files whose change invalidates the recorded figure); a part is (substring of
 # the kernel's name, launches of that kernel in one step, index among them in launch order), and a
 # span made of several launches is the sum of its parts
+_NS = "gear::(anonymous namespace)::"
 TRAFFIC_KERNELS = {
     "gather_pool": ([("k_gather_pool", 1, 0)], ["gather.hip"]),
     "accumulate": ([("k_accumulate", 1, 0)], ["accum.hip"]),
     "embedding_update": ([("k_embedding_chunks", 1, 0), ("k_embedding_spans", 1, 0)], ["update.hip"]),
-    "fwd_gemm_l0": ([("k_gemm_nt_dma<0>", 2, 0)], ["gemm.hip"]),
-    "fwd_gemm_l1": ([("k_gemm_nt_dma<0>", 2, 1)], ["gemm.hip"]),
-    "dgrad_gemm_l1": ([("k_gemm_nt_dma<4>", 1, 0)], ["gemm.hip"]),   # masked by the sign bitmap
-    "dgrad_gemm_emb": ([("k_gemm_nt_dma<3>", 2, 0)], ["gemm.hip"]),
-    "dgrad_gemm_l0": ([("k_gemm_nt_dma<3>", 2, 1)], ["gemm.hip"]),
+    "fwd_gemm_l0": ([("k_gemm_nt_dma<0,", 2, 0)], ["gemm.hip"]),
+    "fwd_gemm_l1": ([("k_gemm_nt_dma<0,", 2, 1)], ["gemm.hip"]),
+    "dgrad_gemm_l1": ([("k_gemm_nt_dma<4,", 1, 0)], ["gemm.hip"]),   # masked by the sign bitmap
+    "dgrad_gemm_emb": ([("k_gemm_nt_dma<3, %sNtNarrow>" % _NS, 1, 0)], ["gemm.hip"]),   # the narrow tile shape
+    "dgrad_gemm_l0": ([("k_gemm_nt_dma<3, %sNtWide>" % _NS, 1, 0)], ["gemm.hip"]),
     "wgrad_gemm": ([("k_gemm_tn_dma_batch", 1, 0)], ["gemm.hip"]),
 }
 # launches whose matrix-pipe occupancy is reported (same part notation)

@@ -328,7 +328,22 @@ __device__ __forceinline__ void epilogue_bf16(const f32x16_v (&acc)[G::TM][G::TN
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 constexpr int DK = 32;                      // k-depth of a stage
 constexpr int DM = 256, DN = 256, DTHREADS = 512;
-constexpr int A_ELEMS = DM * DK, B_ELEMS = DN * DK;
+constexpr int A_ELEMS = DM * DK;
+// Two shapes of the workgroup's tile.  Wide: 256 result columns, four stages, one pair of k-tiles in flight
+// beside the pair that is being multiplied.  Narrow, for results of at most 128 columns (dLoss/dx of the
+// embedding slots): a product of so few columns has little arithmetic per k-tile and waits for its copies,
+// so the B tile is 128 rows, a stage is 24 KB, and six stages keep two pairs in flight.
+// The eight wavefronts cover the tile as 2 x 4 wave tiles of 128 x 64 (wide) or as 4 x 2 of 64 x 64 (narrow),
+// so that all of them have columns in either shape; TMW = 32-row MFMA tiles per wave tile.
+struct NtWide {
+  static constexpr int BN = 256, STAGES = 4, AHEAD = 1, TMW = 4, WAVES_N = 4;
+};
+struct NtNarrow {
+  static constexpr int BN = 128, STAGES = 6, AHEAD = 2, TMW = 2, WAVES_N = 2;
+};
+template <typename C> constexpr int stage_elems() { return A_ELEMS + C::BN * DK; }
+// global_load_lds instructions a wave issues per pair of k-tiles: 16 rows of A twice, 16 rows of B per 128, two k-tiles
+template <typename C> constexpr int dma_per_pair() { return 2 * (2 + C::BN / 128); }
 
 __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
@@ -348,6 +363,7 @@ struct DmaPlan {
 // Two consecutive k-tiles at once: a 128-byte line of an operand row holds the row's share of both,
 // and its two 64-byte halves are requested by back-to-back instructions of one wave, which meet in
 // the vector cache -- one L2 access per line instead of two.
+template <typename C>
 __device__ __forceinline__ void dma_pair(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const DmaPlan &p,
                                          int k0, int k1, bf16_t *s0, bf16_t *s1, int wave) {
 #pragma unroll
@@ -356,7 +372,7 @@ __device__ __forceinline__ void dma_pair(const bf16_t *__restrict__ A, const bf1
     __builtin_amdgcn_global_load_lds((const void *)(A + p.a_off[i] + k1), (lds_ptr_t)(s1 + (i * 8 + wave) * 512), 16, 0, 0);
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < C::BN / 128; ++i) {
     __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + k0), (lds_ptr_t)(s0 + A_ELEMS + (i * 8 + wave) * 512), 16, 0, 0);
     __builtin_amdgcn_global_load_lds((const void *)(B + p.b_off[i] + k1), (lds_ptr_t)(s1 + A_ELEMS + (i * 8 + wave) * 512), 16, 0, 0);
   }
@@ -372,6 +388,30 @@ typedef uint32_t u32x4_v __attribute__((ext_vector_type(4)));
 // m = lane % 32 of the result, the columns n = 8 (e / 4) + 4 (lane / 32) + e % 4 -- four consecutive
 // columns per group of four accumulator elements, which is what its epilogue packs and stores.
 #define MFMA_BF16_T(acc_, a_, b_) MFMA_BF16(acc_, b_, a_)
+
+__device__ __forceinline__ void mma_stage(f32x16_v (&acc)[2][TN], uint32_t a_addr0, uint32_t a_addr1, uint32_t b_addr0,
+                                          uint32_t b_addr1) {
+  u32x4_v p0, p1, q0, q1;   // k-step 0: A rows of the two m-tiles, B rows of the two n-tiles
+  u32x4_v r0, r1, s0, s1;   // k-step 1
+  LDS_READ16(p0, a_addr0, 0);
+  LDS_READ16(p1, a_addr0, 2048);
+  LDS_READ16(q0, b_addr0, 0);
+  LDS_READ16(q1, b_addr0, 2048);
+  LDS_READ16(r0, a_addr1, 0);
+  LDS_READ16(r1, a_addr1, 2048);
+  LDS_READ16(s0, b_addr1, 0);
+  LDS_READ16(s1, b_addr1, 2048);
+  asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(p0), "+v"(p1), "+v"(q0), "+v"(q1)::"memory");
+  MFMA_BF16_T(acc[0][0], p0, q0);
+  MFMA_BF16_T(acc[0][1], p0, q1);
+  MFMA_BF16_T(acc[1][0], p1, q0);
+  MFMA_BF16_T(acc[1][1], p1, q1);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r0), "+v"(r1), "+v"(s0), "+v"(s1)::"memory");
+  MFMA_BF16_T(acc[0][0], r0, s0);
+  MFMA_BF16_T(acc[0][1], r0, s1);
+  MFMA_BF16_T(acc[1][0], r1, s0);
+  MFMA_BF16_T(acc[1][1], r1, s1);
+}
 
 __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_addr0, uint32_t a_addr1, uint32_t b_addr0,
                                           uint32_t b_addr1) {
@@ -418,14 +458,14 @@ __device__ __forceinline__ void mma_stage(f32x16_v (&acc)[TM][TN], uint32_t a_ad
 // columns: below `split` fp32 into `out` [M x split], the rest bf16 into `aux` [M x (N - split)].
 constexpr int PATCH_LD = WN + 8;  // bf16 elements per patch row (144 bytes: the 8-byte writes of a wave spread over all banks)
 
-template <int EPI>
-__device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf16_t *patch, int m0, int n0, int wm,
+template <int EPI, int TMW>
+__device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TMW][TN], bf16_t *patch, int m0, int n0, int wm,
                                                int wn, int lane, int M, int N, const float *__restrict__ bias,
                                                const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
                                                uint8_t *__restrict__ relu_bits, float (&colacc)[8],
-                                               const float *tile_bias, const uint32_t (&hbits)[TM][4]) {
+                                               const float *tile_bias, const uint32_t (&hbits)[TMW][4]) {
   const int c = lane & 31, g = lane >> 5;
-  const int wave_m0 = m0 + wm * WM, wave_n0 = n0 + wn * WN;
+  const int wave_m0 = m0 + wm * (32 * TMW), wave_n0 = n0 + wn * WN;
   // where this wave's columns go
   bool direct_f32 = EPI == EPI_F32, mixed = false;
   int ld_f32 = N, ld_bf = N, col_shift = 0;
@@ -440,7 +480,7 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
   }
   if (mixed) {  // the split falls inside this wave's columns: element by element
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TMW; ++i) {
       const int m = wave_m0 + i * 32 + c;
 #pragma unroll
       for (int j = 0; j < TN; ++j)
@@ -460,7 +500,7 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
   if (direct_f32) {
     // column counts are multiples of 8, so a group of four columns is inside the matrix or outside
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TMW; ++i) {
       const int m = wave_m0 + i * 32 + c;
 #pragma unroll
       for (int j = 0; j < TN; ++j)
@@ -488,10 +528,10 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
     // lane's 16-byte pieces: rows it*8 + lane/8 of each 32-row band, columns (lane%8)*8 .. +7
     const int prow = lane >> 3, cv = (lane & 7) * 8;
     const int n_vec = wave_n0 + cv;
-    Pack16 h[EPI == EPI_MASK ? TM : 1][4];
+    Pack16 h[EPI == EPI_MASK ? TMW : 1][4];
     if constexpr (EPI == EPI_MASK) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TMW; ++i)
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const int m = wave_m0 + i * 32 + it * 8 + prow;
@@ -502,7 +542,7 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
         }
     }
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TMW; ++i) {
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -569,45 +609,55 @@ __device__ __forceinline__ void epilogue_patch(const f32x16_v (&acc)[TM][TN], bf
   }
 }
 
-constexpr int STAGES = 4;
-constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
+constexpr int STAGES = 4;                       // of the TN kernel below
 
-// Tiles t and t + 1 (t even) are copied together into stages t % 4 and (t + 1) % 4 while the pair
-// before them is multiplied: one wait and one barrier per pair.  When nk is odd the last pair's
+// Tiles t and t + 1 (t even) are copied together into stages t % S and (t + 1) % S while the pairs
+// before them are multiplied: one wait and one barrier per pair.  C::AHEAD pairs are in flight beyond the
+// one being multiplied; vector memory operations finish in issue order, so waiting until only the later
+// pairs' instructions are outstanding means the current pair has landed.  When nk is odd the last pair's
 // second half copies the last tile again, into a stage nobody reads.
-template <bool MMA>
-__device__ __forceinline__ void nt_main_loop(f32x16_v (&acc)[TM][TN], const bf16_t *__restrict__ A,
+template <bool MMA, typename C>
+__device__ __forceinline__ void nt_main_loop(f32x16_v (&acc)[C::TMW][TN], const bf16_t *__restrict__ A,
                                              const bf16_t *__restrict__ B, const DmaPlan &plan, bf16_t *lds, int nk,
                                              int wave, const uint32_t (&a_rel)[2], const uint32_t (&b_rel)[2]) {
+  constexpr int SE = stage_elems<C>();
+  static_assert(C::AHEAD == 1 || C::AHEAD == 2, "pairs in flight");
+  static_assert(C::STAGES == 2 * (C::AHEAD + 1), "a pair being multiplied and AHEAD pairs being copied");
   auto issue = [&](int t) {
     const int t1 = min(t + 1, nk - 1);
-    dma_pair(A, B, plan, t * DK, t1 * DK, lds + (t & 3) * STAGE_ELEMS, lds + ((t + 1) & 3) * STAGE_ELEMS, wave);
+    dma_pair<C>(A, B, plan, t * DK, t1 * DK, lds + (t % C::STAGES) * SE, lds + ((t + 1) % C::STAGES) * SE, wave);
   };
   issue(0);
+  if (C::AHEAD == 2 && 2 < nk) issue(2);
   for (int t = 0; t < nk; ++t) {
     if ((t & 1) == 0) {
-      wait_vm<0>();     // this wave's share of tiles t and t + 1 has landed
+      // this wave's share of tiles t and t + 1 has landed
+      if (C::AHEAD == 2 && t + 2 < nk)
+        wait_vm<dma_per_pair<C>()>();
+      else
+        wait_vm<0>();
       block_barrier();  // ... everybody's has, and everybody is done reading tiles t - 2 and t - 1
-      if (t + 2 < nk) issue(t + 2);
+      if (t + 2 * C::AHEAD < nk) issue(t + 2 * C::AHEAD);
     }
-    const uint32_t so = (uint32_t)(t & 3) * (2u * STAGE_ELEMS);
+    const uint32_t so = (uint32_t)(t % C::STAGES) * (2u * SE);
     if constexpr (MMA) mma_stage(acc, a_rel[0] + so, a_rel[1] + so, b_rel[0] + so, b_rel[1] + so);
   }
 }
 
-template <int EPI>
+template <int EPI, typename C = NtWide>
 __global__ void __launch_bounds__(DTHREADS)
 k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M, int N, int K,
               const float *__restrict__ bias, const bf16_t *__restrict__ aux, void *__restrict__ out, int split,
               float *__restrict__ colpart, uint8_t *__restrict__ relu_bits, const int32_t *__restrict__ status) {
   if (*status != 0) return;
-  __shared__ __attribute__((aligned(1024))) bf16_t lds[STAGES * STAGE_ELEMS];   // [stage][A tile | B tile]
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[C::STAGES * stage_elems<C>()];   // [stage][A tile | B tile]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
-  const int n_tiles = (N + DN - 1) / DN;
+  constexpr int TMW = C::TMW, WMW = 32 * C::TMW;   // this shape's wave tile: WMW rows x WN columns
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+  const int n_tiles = (N + C::BN - 1) / C::BN;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / n_tiles) * DM, n0 = (tile % n_tiles) * DN;
+  const int m0 = (tile / n_tiles) * DM, n0 = (tile % n_tiles) * C::BN;
 
   DmaPlan plan;
 #pragma unroll
@@ -625,7 +675,7 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
       const int off = r * DK + (((2 * kk + g) ^ swz(r)) * 8);
-      a_rel[kk] = lds_base + 2u * (uint32_t)(wm * WM * DK + off);
+      a_rel[kk] = lds_base + 2u * (uint32_t)(wm * WMW * DK + off);
       b_rel[kk] = lds_base + 2u * (uint32_t)(A_ELEMS + wn * WN * DK + off);
     }
   }
@@ -633,30 +683,30 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
   // What the epilogue needs from global memory is requested here, so that it arrives while the
   // products run: the tile's biases go to LDS (the barriers of the main loop make them visible), the
   // sign bits of the lane's sixteen 16-byte pieces (eight bits each) stay in registers.
-  __shared__ float s_bias[EPI == EPI_BIAS_RELU ? DN : 1];
+  __shared__ float s_bias[EPI == EPI_BIAS_RELU ? C::BN : 1];
   if constexpr (EPI == EPI_BIAS_RELU) {
-    if (tid < DN) s_bias[tid] = n0 + tid < N ? bias[n0 + tid] : 0.0f;
+    if (tid < C::BN) s_bias[tid] = n0 + tid < N ? bias[n0 + tid] : 0.0f;
   }
-  uint32_t hbits[TM][4];
+  uint32_t hbits[TMW][4];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TMW; ++i)
 #pragma unroll
     for (int it = 0; it < 4; ++it) hbits[i][it] = 0u;
   if constexpr (EPI == EPI_MASK_BITS) {
     const uint8_t *bits = reinterpret_cast<const uint8_t *>(aux);
     const int n_vec = n0 + wn * WN + (lane & 7) * 8;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TMW; ++i)
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
-        const int m = m0 + wm * WM + i * 32 + it * 8 + (lane >> 3);
+        const int m = m0 + wm * WMW + i * 32 + it * 8 + (lane >> 3);
         if (m < M && n_vec < N) hbits[i][it] = bits[(size_t)m * (N >> 3) + (n_vec >> 3)];
       }
   }
 
-  f32x16_v acc[TM][TN];
+  f32x16_v acc[TMW][TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TMW; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -664,16 +714,20 @@ k_gemm_nt_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, int M,
 
   // in a tile whose right part lies beyond N, the waves without columns copy tiles and meet the
   // barriers but skip the operand reads and the products
-  if (n0 + wn * WN < N)
-    nt_main_loop<true>(acc, A, B, plan, lds, K / DK, wave, a_rel, b_rel);
+  const bool has_columns = n0 + wn * WN < N;
+  if (has_columns)
+    nt_main_loop<true, C>(acc, A, B, plan, lds, K / DK, wave, a_rel, b_rel);
   else
-    nt_main_loop<false>(acc, A, B, plan, lds, K / DK, wave, a_rel, b_rel);
+    nt_main_loop<false, C>(acc, A, B, plan, lds, K / DK, wave, a_rel, b_rel);
   wait_vm<0>();
-  block_barrier();  // every wave is done with the operand tiles: stage 0 becomes the output patches
+  block_barrier();  // every wave is done with the operand tiles: the first stages become the output patches
+  static_assert((8 * 32 * PATCH_LD) * 2 + 8 * 64 * 4 <= C::STAGES * stage_elems<C>() * 2, "patches and column sums fit");
   bf16_t *patch = lds + wave * 32 * PATCH_LD;
   float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  epilogue_patch<EPI>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, relu_bits, colacc, s_bias, hbits);
+  if (has_columns)
+    epilogue_patch<EPI, TMW>(acc, patch, m0, n0, wm, wn, lane, M, N, bias, aux, out, split, relu_bits, colacc, s_bias, hbits);
   if constexpr (EPI == EPI_MASK || EPI == EPI_MASK_BITS) {
+    static_assert(C::WAVES_N == 4, "the column sums below add the two wave rows of the wide shape");
     if (colpart) {
       // colpart[m-tile][n] = sum over the tile's rows of the stored values: lanes that share lane % 8
       // hold the same eight columns, then the two waves that share the columns are added
@@ -1065,21 +1119,31 @@ hipError_t run_nt(const void *A, const void *B, int M, int N, int K, int epi, co
                   void *out, int split, float *colpart, uint8_t *relu_bits, const int32_t *status, hipStream_t s) {
   if constexpr (sizeof(T) == 2) {
     if (K % DK == 0) {
-      const dim3 grid(((M + DM - 1) / DM) * ((N + DN - 1) / DN));
-#define GEAR_DMA(E)                                                                                               \
-  hipLaunchKernelGGL((k_gemm_nt_dma<E>), grid, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, \
+      const bool narrow = N <= NtNarrow::BN && (epi == EPI_DX || epi == EPI_F32);
+      const dim3 grid(((M + DM - 1) / DM) * (narrow ? 1 : (N + DN - 1) / DN));
+#define GEAR_DMA_C(E, C)                                                                                              \
+  hipLaunchKernelGGL((k_gemm_nt_dma<E, C>), grid, dim3(DTHREADS), 0, s, (const bf16_t *)A, (const bf16_t *)B, M, N, K, \
                      bias, (const bf16_t *)aux, out, split, colpart, relu_bits, status)
+#define GEAR_DMA(E) GEAR_DMA_C(E, NtWide)
       if (epi == EPI_BIAS_RELU)
         GEAR_DMA(EPI_BIAS_RELU);
       else if (epi == EPI_MASK)
         GEAR_DMA(EPI_MASK);
       else if (epi == EPI_MASK_BITS)
         GEAR_DMA(EPI_MASK_BITS);
-      else if (epi == EPI_DX)
-        GEAR_DMA(EPI_DX);
-      else
-        GEAR_DMA(EPI_F32);
+      else if (epi == EPI_DX) {
+        if (narrow)
+          GEAR_DMA_C(EPI_DX, NtNarrow);
+        else
+          GEAR_DMA(EPI_DX);
+      } else {
+        if (narrow)
+          GEAR_DMA_C(EPI_F32, NtNarrow);
+        else
+          GEAR_DMA(EPI_F32);
+      }
 #undef GEAR_DMA
+#undef GEAR_DMA_C
       return hipGetLastError();
     }
   }

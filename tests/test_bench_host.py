@@ -15,6 +15,8 @@ import bench  # noqa: E402
 from gear_inputs import get_workload  # noqa: E402
 from gear_inputs.pageviews import PageViewBatch  # noqa: E402
 
+NS = "gear::(anonymous namespace)::"   # as the kernels' names come out of the profiler
+
 
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
@@ -63,10 +65,10 @@ def test_counter_files_become_bytes_per_launch(tmp_path, monkeypatch):
     monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "traffic.json"))
     monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(tmp_path / "traffic.txt"))
     ns = "void gear::(anonymous namespace)::"
-    step = [("k_gather_pool<float, unsigned short, unsigned short>(int)", 10.0), ("k_gemm_nt_dma<0>(x)", 20.0),
-            ("k_gemm_nt_dma<0>(x)", 30.0), ("k_gemm_nt_dma<4>(x)", 40.0), ("k_gemm_nt_dma<3>(x)", 50.0),
+    step = [("k_gather_pool<float, unsigned short, unsigned short>(int)", 10.0), ("k_gemm_nt_dma<0, %sNtWide>(x)" % NS, 20.0),
+            ("k_gemm_nt_dma<0, %sNtWide>(x)" % NS, 30.0), ("k_gemm_nt_dma<4, %sNtWide>(x)" % NS, 40.0), ("k_gemm_nt_dma<3, %sNtNarrow>(x)" % NS, 50.0),
             ("k_embedding_chunks<float>(x)", 5.0), ("k_embedding_spans<float>(x)", 7.0),
-            ("k_gemm_nt_dma<3>(x)", 60.0), ("k_gemm_tn_dma_batch(x)", 70.0), ("k_accumulate<unsigned short>(x)", 80.0)]
+            ("k_gemm_nt_dma<3, %sNtWide>(x)" % NS, 60.0), ("k_gemm_tn_dma_batch(x)", 70.0), ("k_accumulate<unsigned short>(x)", 80.0)]
     rows = [(ns + n, v) for n, v in step] + [(ns + n, v + 2.0) for n, v in step] + [(ns + "k_refresh(x)", 1000.0)]
     _counter_csv(tmp_path / "f.csv", "FETCH_SIZE", rows)
     _counter_csv(tmp_path / "w.csv", "WRITE_SIZE", [(n, 2 * v) for n, v in rows])
@@ -94,7 +96,7 @@ def test_mfma_counters_become_occupancy(tmp_path, monkeypatch):
     """busy cycles over all SIMDs against the cycles on the device (the counter sums the XCDs)."""
     monkeypatch.setattr(bench, "MFMA_SUMMARY", str(tmp_path / "mfma.txt"))
     ns = "void gear::(anonymous namespace)::"
-    names = ["k_gemm_nt_dma<0>(x)", "k_gemm_nt_dma<0>(x)", "k_gemm_nt_dma<4>(x)", "k_gemm_nt_dma<3>(x)", "k_gemm_nt_dma<3>(x)",
+    names = ["k_gemm_nt_dma<0, %sNtWide>(x)" % NS, "k_gemm_nt_dma<0, %sNtWide>(x)" % NS, "k_gemm_nt_dma<4, %sNtWide>(x)" % NS, "k_gemm_nt_dma<3, %sNtNarrow>(x)" % NS, "k_gemm_nt_dma<3, %sNtWide>(x)" % NS,
              "k_gemm_tn_dma_batch(x)"]
     with open(tmp_path / "m.csv", "w", newline="") as f:
         w = csv.DictWriter(f, fieldnames=["Dispatch_Id", "Kernel_Name", "Counter_Name", "Counter_Value"])

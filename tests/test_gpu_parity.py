@@ -987,7 +987,10 @@ def test_refresh_overwrites_rows_and_nothing_else():
                                    # more tiles than compute units (a workgroup walks several), ragged in both directions
                                    (70000, 328, 160), (66000, 520, 96),
                                    # too few 256 x 128 tiles for every compute unit: the 128 x 128 geometry
-                                   (16500, 264, 200)])
+                                   (16500, 264, 200),
+                                   # at most 128 result columns, K a multiple of 32: the fp32-result bf16 product takes the
+                                   # narrow tile with two pairs of k-tiles in flight (1, 2, 3, 5 and 32 k-tiles)
+                                   (1000, 128, 32), (2048, 64, 64), (300, 72, 96), (517, 120, 160), (70000, 128, 1024)])
 def test_gemm_forms_against_fp32_matmul(dtype, M, N, K):
     """Both forms against a plain fp32/fp64 matmul of the same operands (ragged tiles included)."""
     td = torch.bfloat16 if dtype == "bf16" else torch.float32
